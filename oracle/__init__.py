@@ -51,6 +51,8 @@ def _load():
         lib.oracle_get_grads.argtypes = [vp, ctypes.c_int, dp, dp]
         lib.oracle_get_buffer.argtypes = [vp, ctypes.c_int, ctypes.c_int, ctypes.c_int, fp]
         lib.oracle_set_buffer.argtypes = [vp, ctypes.c_int, ctypes.c_int, ctypes.c_int, fp]
+        lib.oracle_get_history.argtypes = [vp, vp]
+        lib.oracle_set_history.argtypes = [vp, vp]
         lib.oracle_get_tick.restype = ctypes.c_long
         lib.oracle_get_tick.argtypes = [vp]
         lib.oracle_set_tick.argtypes = [vp, ctypes.c_long]
@@ -60,6 +62,11 @@ def _load():
         lib.oracle_set_adam.argtypes = [vp, ctypes.c_double, ctypes.c_double, ctypes.c_double]
         lib.oracle_get_moments.argtypes = [vp, ctypes.c_int, fp, fp, fp, fp]
         lib.oracle_set_moments.argtypes = [vp, ctypes.c_int, fp, fp, fp, fp]
+        lib.oracle_clone.restype = vp
+        lib.oracle_clone.argtypes = [vp]
+        lib.oracle_set_kink_band.argtypes = [vp, ctypes.c_double, ctypes.c_int, ctypes.c_long]
+        lib.oracle_take_kink_events.restype = ctypes.c_long
+        lib.oracle_take_kink_events.argtypes = [vp, ctypes.POINTER(ctypes.c_long)]
         lib.oracle_take_kink_margin.restype = ctypes.c_double
         lib.oracle_take_kink_margin.argtypes = [vp]
         lib.oracle_step.argtypes = [vp, fp, vp, ctypes.c_int, fp, fp, ip]
@@ -187,6 +194,20 @@ class Oracle:
         a = np.ascontiguousarray(a, dtype=np.float32).reshape(self.S, n)
         self.lib.oracle_set_buffer(self.h, 0 if which == "act" else 1, stage, half, _fp(a))
 
+    def get_history(self):
+        """The targets of the last target_delay ticks, oldest first, as raw 4-byte elements (float32 view)."""
+        per = self.S * (self.stage_out[-1] if self.loss == LOSS_MSE else 1)
+        a = np.zeros((max(self.k, 0) * per,), dtype=np.float32)
+        if a.size:
+            self.lib.oracle_get_history(self.h, a.ctypes.data_as(ctypes.c_void_p))
+        return a
+
+    def set_history(self, a):
+        a = np.ascontiguousarray(a)
+        assert a.dtype.itemsize == 4
+        if a.size:
+            self.lib.oracle_set_history(self.h, a.ctypes.data_as(ctypes.c_void_p))
+
     @property
     def tick(self):
         return int(self.lib.oracle_get_tick(self.h))
@@ -201,6 +222,26 @@ class Oracle:
     def take_kink_margin(self) -> float:
         """Smallest |z| at which a ReLU derivative entered a non-zero delta since the last call (diagnostic)."""
         return float(self.lib.oracle_take_kink_margin(self.h))
+
+    def set_kink_band(self, eps: float, side: int = 0, cap: int = 4096):
+        """Test diagnostic: record ReLU units with |z| < eps and a non-zero error signal; side +1 / -1 also takes
+        1 / 0 as their derivative (side 0 leaves the arithmetic alone)."""
+        self._band_cap = cap
+        self.lib.oracle_set_kink_band(self.h, float(eps), int(side), cap)
+
+    def take_kink_events(self):
+        """(count, int64 array [min(count, cap)][3] of (tick, layer, stream * out_size + unit)) since the last call."""
+        cap = getattr(self, "_band_cap", 0)
+        buf = np.zeros((max(cap, 1), 3), dtype=np.int64)
+        cnt = int(self.lib.oracle_take_kink_events(self.h, buf.ctypes.data_as(ctypes.POINTER(ctypes.c_long))))
+        return cnt, buf[:min(cnt, cap)]
+
+    def clone(self):
+        """Deep copy: weights, moments, buffers, lanes, target history, tick and switches."""
+        import copy
+        c = copy.copy(self)
+        c.h = self.lib.oracle_clone(self.h)
+        return c
 
     def reset(self):
         self.lib.oracle_reset(self.h)

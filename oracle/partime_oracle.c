@@ -78,6 +78,11 @@ typedef struct {
   float **err[2];              /* err[half][stage]  [S][stage in size]     */
   long tick;
   double kink_margin;          /* diagnostic only: smallest |z| at which a ReLU derivative was taken with g != 0 */
+  /* test diagnostic, no part of the method (see oracle_set_kink_band) */
+  double band_eps;             /* half-width of the band around z = 0; 0 = no band                               */
+  int band_side;               /* 0: ReLU'(z) = [z > 0] everywhere; +1 / -1: inside the band the derivative is 1 / 0 */
+  long n_events, cap_events;   /* ReLU units found inside the band with a non-zero error signal                  */
+  long *events;                /* triples (tick, layer, stream * out_size + unit), the first cap_events of them  */
   long tgt_elems;              /* elements of one tick's target            */
   unsigned char *tgt_hist;     /* last k targets, oldest first             */
   double *g, *g2;              /* scratch [S][max size]                    */
@@ -125,6 +130,13 @@ static double dphi(int act, double z) {
     return cdf + z * pdf;
   }
   return 1.0;
+}
+
+/* derivative as the stage takes it: ReLU'(z) = [z > 0] (0 at z = 0), except inside the test band (see
+ * oracle_set_kink_band), where the derivative is the one-sided value the caller chose */
+static double dphi_at(const net_t *n, int act, double z) {
+  if (act == A_RELU && n->band_side != 0 && fabs(z) < n->band_eps) return n->band_side > 0 ? 1.0 : 0.0;
+  return dphi(act, z);
 }
 
 /* ---- one layer: forward, input-gradient, weight-gradient ---------------- */
@@ -290,7 +302,8 @@ static long stage_out(const net_t *n, int h) {
 void *oracle_create(int n_layers, const int *desc, int depth, const int *balance, int S,
                     int w_bf16, int loss, float lr, int k) {
   net_t *n = (net_t *)calloc(1, sizeof(net_t));
-  if (n) n->kink_margin = 1e300;
+  if (!n) return NULL;
+  n->kink_margin = 1e300;
   n->n_layers = n_layers; n->depth = depth; n->S = S; n->w_bf16 = w_bf16;
   n->loss = loss; n->lr = (double)lr; n->k = k;
   n->layers = (layer_t *)calloc(n_layers, sizeof(layer_t));
@@ -376,7 +389,68 @@ void oracle_destroy(void *p) {
   }
   free(n->stage_of);
   free(n->layers); free(n->first); free(n->count); free(n->g); free(n->g2); free(n->tgt_hist);
+  free(n->events);
   free(n);
+}
+
+static void *dup_mem(const void *src, size_t bytes) {
+  if (!src) return NULL;
+  void *d = malloc(bytes ? bytes : 1);
+  memcpy(d, src, bytes);
+  return d;
+}
+
+/* Deep copy of a pipeline with everything it carries between ticks (weights, moments, both halves of every buffer
+ * and lane, target history, tick, switches); the gradients of the last tick are not carried over.  For the tests:
+ * several continuations of one state. */
+void *oracle_clone(const void *p) {
+  const net_t *n = (const net_t *)p;
+  net_t *c = (net_t *)malloc(sizeof(net_t));
+  *c = *n;
+  const int D = n->depth, S = n->S;
+  c->layers = (layer_t *)dup_mem(n->layers, (size_t)n->n_layers * sizeof(layer_t));
+  c->first = (int *)dup_mem(n->first, (size_t)D * sizeof(int));
+  c->count = (int *)dup_mem(n->count, (size_t)D * sizeof(int));
+  c->stage_of = (int *)dup_mem(n->stage_of, (size_t)n->n_layers * sizeof(int));
+  c->g = (double *)calloc((size_t)S * n->max_size, sizeof(double));
+  c->g2 = (double *)calloc((size_t)S * n->max_size, sizeof(double));
+  c->tgt_hist = (unsigned char *)dup_mem(n->tgt_hist, (size_t)(n->k > 0 ? n->k : 1) * n->tgt_elems * 4);
+  c->events = (long *)dup_mem(n->events, (size_t)n->cap_events * 3 * sizeof(long));
+  for (int q = 0; q < 2; ++q) {
+    c->act[q] = (float **)calloc(D, sizeof(float *));
+    c->err[q] = (float **)calloc(D, sizeof(float *));
+    for (int h = 0; h < D; ++h) {
+      c->act[q][h] = (float *)dup_mem(n->act[q][h], (size_t)S * stage_out(n, h) * sizeof(float));
+      c->err[q][h] = (float *)dup_mem(n->err[q][h], (size_t)S * stage_in(n, h) * sizeof(float));
+    }
+  }
+  for (int i = 0; i < n->n_layers; ++i) {
+    const layer_t *l = &n->layers[i];
+    layer_t *d = &c->layers[i];
+    const size_t so = (size_t)S * l->out_size;
+    d->W = (float *)dup_mem(l->W, l->n_w * sizeof(float));
+    d->b = (float *)dup_mem(l->b, l->n_b * sizeof(float));
+    /* scratch of a tick (rebuilt by every tick before it is read): fresh, not copied */
+    d->dW = (double *)calloc(l->n_w, sizeof(double));
+    d->db = (double *)calloc(l->n_b, sizeof(double));
+    d->mW = (float *)dup_mem(l->mW, l->n_w * sizeof(float));
+    d->vW = (float *)dup_mem(l->vW, l->n_w * sizeof(float));
+    d->mb = (float *)dup_mem(l->mb, l->n_b * sizeof(float));
+    d->vb = (float *)dup_mem(l->vb, l->n_b * sizeof(float));
+    d->u = (double *)calloc((size_t)S * l->in_size, sizeof(double));
+    d->z = (double *)calloc(so, sizeof(double));
+    d->o = (double *)calloc(so, sizeof(double));
+    d->gskip = (double *)calloc(so, sizeof(double));
+    for (int q = 0; q < 2 && l->skip_src >= 0; ++q) {
+      d->lane_a[q] = (float **)calloc(D, sizeof(float *));
+      d->lane_e[q] = (float **)calloc(D, sizeof(float *));
+      for (int h = 0; h < D; ++h) {
+        d->lane_a[q][h] = (float *)dup_mem(l->lane_a[q][h], so * sizeof(float));
+        d->lane_e[q][h] = (float *)dup_mem(l->lane_e[q][h], so * sizeof(float));
+      }
+    }
+  }
+  return c;
 }
 
 void oracle_set_weights(void *p, int layer, const float *W, const float *b) {
@@ -405,6 +479,15 @@ void oracle_set_buffer(void *p, int which, int stage, int half, const float *src
   net_t *n = (net_t *)p;
   long sz = (long)n->S * (which == 0 ? stage_out(n, stage) : stage_in(n, stage));
   memcpy(which == 0 ? n->act[half][stage] : n->err[half][stage], src, sz * sizeof(float));
+}
+/* the targets of the last k ticks, oldest first (k x one tick's targets, 4-byte elements) */
+void oracle_get_history(void *p, void *dst) {
+  net_t *n = (net_t *)p;
+  if (n->k > 0) memcpy(dst, n->tgt_hist, (size_t)n->k * n->tgt_elems * 4);
+}
+void oracle_set_history(void *p, const void *src) {
+  net_t *n = (net_t *)p;
+  if (n->k > 0) memcpy(n->tgt_hist, src, (size_t)n->k * n->tgt_elems * 4);
 }
 long oracle_get_tick(void *p) { return ((net_t *)p)->tick; }
 void oracle_set_tick(void *p, long t) { ((net_t *)p)->tick = t; }
@@ -443,8 +526,32 @@ double oracle_take_kink_margin(void *p) {
   n->kink_margin = 1e300;
   return m;
 }
+/* Test diagnostic, no part of the method.  Eq. 9 takes the derivative at this tick's z, and ReLU' jumps at 0: an
+ * implementation that sums z in fp32, or in another order, can land on the other side of 0 when |z| is within
+ * its rounding error, and then takes the other one-sided derivative; both are derivatives of the function it
+ * evaluated.  With eps > 0 every ReLU unit with |z| < eps and a non-zero error signal is recorded (tick, layer,
+ * stream * out_size + unit).  side = 0 leaves the arithmetic alone (ReLU'(z) = [z > 0]); side = +1 / -1 takes 1 / 0
+ * as the derivative of the recorded units, so that a test can tell which results depend on those units at all. */
+void oracle_set_kink_band(void *p, double eps, int side, long cap) {
+  net_t *n = (net_t *)p;
+  n->band_eps = eps; n->band_side = side;
+  free(n->events);
+  n->cap_events = cap > 0 ? cap : 0;
+  n->events = (long *)calloc((size_t)(n->cap_events ? n->cap_events : 1) * 3, sizeof(long));
+  n->n_events = 0;
+}
+/* number of recorded units since the last call; the first min(count, cap) triples are copied to buf */
+long oracle_take_kink_events(void *p, long *buf) {
+  net_t *n = (net_t *)p;
+  const long cnt = n->n_events, m = cnt < n->cap_events ? cnt : n->cap_events;
+  if (buf && m > 0) memcpy(buf, n->events, (size_t)m * 3 * sizeof(long));
+  n->n_events = 0;
+  return cnt;
+}
+
 void oracle_reset(void *p) {
   net_t *n = (net_t *)p;
+  n->n_events = 0;
   for (int q = 0; q < 2; ++q)
     for (int h = 0; h < n->depth; ++h) {
       memset(n->act[q][h], 0, (size_t)n->S * stage_out(n, h) * sizeof(float));
@@ -555,10 +662,20 @@ static void stage_tick(net_t *n, int h, const float *x_t, const void *target_use
         for (long i = 0; i < osz; ++i) l->lane_e[cur][h][i] = (float)g[i];
     }
     double *delta = n->g2; /* o is no longer needed */
-    for (long i = 0; i < (long)S * l->out_size; ++i) delta[i] = opr(n, g[i] * dphi(l->act, l->z[i]));
+    for (long i = 0; i < (long)S * l->out_size; ++i) delta[i] = opr(n, g[i] * dphi_at(n, l->act, l->z[i]));
     if (l->act == A_RELU)
-      for (long i = 0; i < (long)S * l->out_size; ++i)
-        if (g[i] != 0.0 && fabs(l->z[i]) < n->kink_margin) n->kink_margin = fabs(l->z[i]);
+      for (long i = 0; i < (long)S * l->out_size; ++i) {
+        if (g[i] == 0.0) continue;
+        const double az = fabs(l->z[i]);
+        if (az < n->kink_margin) n->kink_margin = az;
+        if (az < n->band_eps) {
+          if (n->n_events < n->cap_events) {
+            long *e = n->events + 3 * n->n_events;
+            e[0] = n->tick; e[1] = f + j; e[2] = i;
+          }
+          n->n_events += 1;
+        }
+      }
     for (int s = 0; s < S; ++s)
       layer_weight_grad(l, l->u + s * l->in_size, delta + s * l->out_size, 1.0 / (double)S, l->dW, l->db);
     if (j > 0 || h > 0)

@@ -543,6 +543,69 @@ def test_kink_margin_diagnostic_reports_smallest_relu_preactivation():
     assert ref.take_kink_margin() == 0.125
 
 
+def test_kink_band_records_units_near_zero_and_takes_the_chosen_one_sided_derivative():
+    """The band diagnostic of the GPU parity tests on a one-stage net with hand-set pre-activations (all values dyadic):
+    units inside the band with a non-zero error signal are recorded, side 0 leaves ReLU'(z) = [z > 0], side +1 / -1
+    takes 1 / 0 for exactly those units; everything else is untouched."""
+    layers = [ps.LayerSpec(ps.DENSE, ps.ACT_RELU, 2, 4)]
+    W = np.array([[1.0, 0.0], [0.0, -2.0], [0.5, 0.5], [0.25, 0.0]], dtype=np.float32)
+    b = np.array([0.0, 0.0, -0.5 + 2.0 ** -20, -0.0625 - 2.0 ** -20], dtype=np.float32)
+    x = np.array([[[0.25, 0.75]]], dtype=np.float32)           # z = (0.25, -1.5, +2^-20, -2^-20)
+    y = np.zeros((1, 1, 4), dtype=np.float32)                  # MSE: g = 2 (o - y) / 4 = o / 2
+    y[0, 0, 3] = 1.0                                           # unit 3 has o = 0, so g = -0.5 (non-zero)
+    y[0, 0, 1] = 0.0                                           # unit 1: o = 0, y = 0: g = 0, never recorded
+    grads = {}
+    for side in (0, 1, -1):
+        ref = orc.Oracle(layers, [W], [b], loss=ps.LOSS_MSE, lr=0.0)
+        ref.set_kink_band(2.0 ** -10, side)
+        ref.step(x, y)
+        cnt, ev = ref.take_kink_events()
+        assert cnt == 2 and ev.tolist() == [[0, 0, 2], [0, 0, 3]]        # (tick, layer, unit); unit 0 and 1 are far / silent
+        assert ref.take_kink_events()[0] == 0                            # taking them resets the count
+        grads[side] = ref.get_grads(0)[1]                                # db = delta
+    g2, g3 = 2.0 ** -21, -0.5                                            # g = o / 2 for unit 2, (0 - 1) / 2 for unit 3
+    assert grads[0].tolist() == [0.125, 0.0, g2, 0.0]                    # [z > 0]: unit 2 active, unit 3 not
+    assert grads[1].tolist() == [0.125, 0.0, g2, g3]                     # band counted as active
+    assert grads[-1].tolist() == [0.125, 0.0, 0.0, 0.0]                  # band counted as inactive
+    # a band that the units are outside of changes nothing and records nothing
+    ref = orc.Oracle(layers, [W], [b], loss=ps.LOSS_MSE, lr=0.0)
+    ref.set_kink_band(2.0 ** -21, 1)
+    ref.step(x, y)
+    assert ref.take_kink_events()[0] == 0 and ref.get_grads(0)[1].tolist() == grads[0].tolist()
+
+
+@pytest.mark.parametrize("adam", [None, (0.9, 0.999, 1e-8)])
+def test_clone_continues_exactly_like_the_original(adam):
+    """A clone carries everything that crosses a tick boundary: weights, moments, both halves of the buffers, skip lanes,
+    the target history and the tick; stepping both gives bit-identical results, and they do not share memory."""
+    layers = skip_mlp_layers([6, 8, 8, 8, 5], {2: 1}, ps.ACT_RELU)
+    Ws, bs = ps.init_weights(layers, 3)
+    ref = orc.Oracle(layers, Ws, bs, loss=ps.LOSS_CE, lr=0.05, target_delay=2, balance=[1, 2, 1], adam=adam)
+    x = rand_stream(16, 1, 6, 5)
+    tg = targets_for(ps.LOSS_CE, 16, 1, 5, 5)
+    ref.step(x[:9], tg[:9])
+    twin = ref.clone()
+    assert twin.tick == 9
+    o1, l1 = ref.step(x[9:], tg[9:])
+    w_after = ref.get_weights(0)[0].copy()
+    o2, l2 = twin.step(x[9:], tg[9:])                                   # the original has moved on: no shared state
+    assert np.array_equal(o1, o2) and np.array_equal(l1, l2)
+    for i in range(len(layers)):
+        for a, c in zip(ref.get_weights(i), twin.get_weights(i)):
+            assert np.array_equal(a, c)
+        if adam:
+            for a, c in zip(ref.get_moments(i), twin.get_moments(i)):
+                assert np.array_equal(a, c)
+    assert np.array_equal(ref.get_weights(0)[0], w_after)
+
+
+def skip_mlp_layers(widths, skips, act):
+    layers = ps.mlp(widths, act)
+    for dst, src in skips.items():
+        layers[dst].skip_from = src
+    return layers
+
+
 # ----------------------------------------------------------------------------- skip connections (Sec. V-C)
 
 def skip_mlp(widths, skips, act):
