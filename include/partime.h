@@ -124,6 +124,10 @@ int partime_set_state(partime_ctx *ctx, int layer, const float *w_host, const fl
  * Synchronous access to the inter-stage buffers, for checkpoints and single-tick checks.
  *   which = 0: what stage `stage` published for stage+1 (activation, [S][stage out size])
  *   which = 1: the input-error stage `stage` published for stage-1 ([S][stage in size])
+ *   which = 2: the targets of the last target_delay ticks, oldest first, that the coming ticks will be scored
+ *              against (text under Eq. 10 with the pairing of Eq. 7): target_delay x one tick's targets, copied as
+ *              the 4-byte elements they were supplied in (fp32, or int32 class ids behind the float pointer);
+ *              stage and half are ignored; nothing is copied when target_delay = 0
  *   half  = 0/1: the half written at even / odd ticks.
  * Pipelines of 64 and more streams keep activations rounded to bf16: those come back, and are taken, as such.
  */

@@ -79,7 +79,7 @@ typedef struct {
   long tick;
   double kink_margin;          /* diagnostic only: smallest |z| at which a ReLU derivative was taken with g != 0 */
   /* test diagnostic, no part of the method (see oracle_set_kink_band) */
-  double band_eps;             /* half-width of the band around z = 0; 0 = no band                               */
+  double band_eps;             /* half-width of the band around z = 0, relative to sum |w u| + |b|; 0 = no band  */
   int band_side;               /* 0: ReLU'(z) = [z > 0] everywhere; +1 / -1: inside the band the derivative is 1 / 0 */
   long n_events, cap_events;   /* ReLU units found inside the band with a non-zero error signal                  */
   long *events;                /* triples (tick, layer, stream * out_size + unit), the first cap_events of them  */
@@ -132,12 +132,6 @@ static double dphi(int act, double z) {
   return 1.0;
 }
 
-/* derivative as the stage takes it: ReLU'(z) = [z > 0] (0 at z = 0), except inside the test band (see
- * oracle_set_kink_band), where the derivative is the one-sided value the caller chose */
-static double dphi_at(const net_t *n, int act, double z) {
-  if (act == A_RELU && n->band_side != 0 && fabs(z) < n->band_eps) return n->band_side > 0 ? 1.0 : 0.0;
-  return dphi(act, z);
-}
 
 /* ---- one layer: forward, input-gradient, weight-gradient ---------------- */
 
@@ -265,6 +259,49 @@ static void layer_weight_grad(const layer_t *l, const double *u, const double *d
       db[r] += scale * delta[r];
     }
   }
+}
+
+/* ---- test band around z = 0 (see oracle_set_kink_band): how large the terms of one unit's sum are ---------- */
+
+/* sum_i |w_i u_i| + |b| of output unit r (for stream input u): the scale the rounding error of any way of summing
+ * z_r = sum_i w_i u_i + b is proportional to */
+static double unit_abs_sum(const layer_t *l, const double *u, long r) {
+  double acc = 0.0;
+  if (l->kind == K_DENSE) {
+    const float *w = l->W + r * (long)l->in_dim;
+    for (long c = 0; c < l->in_dim; ++c) acc += fabs((double)w[c] * u[c]);
+    return acc + fabs((double)l->b[r]);
+  }
+  if (l->kind == K_CONV3) {
+    const int H = l->hh, Wd = l->ww;
+    const int co = (int)(r / ((long)H * Wd)), y = (int)((r / Wd) % H), x = (int)(r % Wd);
+    for (int ci = 0; ci < l->c_in; ++ci)
+      for (int ky = 0; ky < 3; ++ky)
+        for (int kx = 0; kx < 3; ++kx) {
+          int yy = y + ky - 1, xx = x + kx - 1;
+          if (yy < 0 || yy >= H || xx < 0 || xx >= Wd) continue;
+          acc += fabs((double)l->W[((co * (long)l->c_in + ci) * 3 + ky) * 3 + kx] * u[(ci * (long)H + yy) * Wd + xx]);
+        }
+    return acc + fabs((double)l->b[co]);
+  }
+  const long HW = (long)l->hh * l->ww;
+  for (int c = 0; c < l->c_in; ++c) {
+    double m = 0.0;
+    for (long p = 0; p < HW; ++p) m += u[c * HW + p];
+    acc += fabs((double)l->W[r * (long)l->c_in + c] * (m / (double)HW));
+  }
+  return acc + fabs((double)l->b[r]);
+}
+
+/* an upper bound of unit_abs_sum over all units of the layer (cheap: used to skip the units far from 0) */
+static double layer_abs_bound(const layer_t *l, const double *u) {
+  double mw = 0.0, mb = 0.0, su = 0.0, mu = 0.0;
+  for (long i = 0; i < l->n_w; ++i) { double a = fabs((double)l->W[i]); if (a > mw) mw = a; }
+  for (long i = 0; i < l->n_b; ++i) { double a = fabs((double)l->b[i]); if (a > mb) mb = a; }
+  for (long i = 0; i < l->in_size; ++i) { double a = fabs(u[i]); su += a; if (a > mu) mu = a; }
+  if (l->kind == K_DENSE) return mw * su + mb;
+  if (l->kind == K_CONV3) return mw * 9.0 * l->c_in * mu + mb;
+  return mw * l->c_in * mu + mb;
 }
 
 /* ---- loss heads (text under Eq. 10: g_D = dL/do at this tick's output) -- */
@@ -527,11 +564,13 @@ double oracle_take_kink_margin(void *p) {
   return m;
 }
 /* Test diagnostic, no part of the method.  Eq. 9 takes the derivative at this tick's z, and ReLU' jumps at 0: an
- * implementation that sums z in fp32, or in another order, can land on the other side of 0 when |z| is within
- * its rounding error, and then takes the other one-sided derivative; both are derivatives of the function it
- * evaluated.  With eps > 0 every ReLU unit with |z| < eps and a non-zero error signal is recorded (tick, layer,
- * stream * out_size + unit).  side = 0 leaves the arithmetic alone (ReLU'(z) = [z > 0]); side = +1 / -1 takes 1 / 0
- * as the derivative of the recorded units, so that a test can tell which results depend on those units at all. */
+ * implementation that sums z = sum_i w_i u_i + b in fp32, or in another order, can land on the other side of 0 when
+ * |z| is within its rounding error, and then takes the other one-sided derivative; both are derivatives of the
+ * function it evaluated.  The rounding error of a sum is proportional to the size of its terms, so the band is
+ * relative: with eps > 0 every ReLU unit with |z| < eps * (sum_i |w_i u_i| + |b|) and a non-zero error signal is
+ * recorded (tick, layer, stream * out_size + unit).  side = 0 leaves the arithmetic alone (ReLU'(z) = [z > 0]);
+ * side = +1 / -1 takes 1 / 0 as the derivative of the recorded units, so that a test can tell which results depend
+ * on those units at all. */
 void oracle_set_kink_band(void *p, double eps, int side, long cap) {
   net_t *n = (net_t *)p;
   n->band_eps = eps; n->band_side = side;
@@ -662,18 +701,25 @@ static void stage_tick(net_t *n, int h, const float *x_t, const void *target_use
         for (long i = 0; i < osz; ++i) l->lane_e[cur][h][i] = (float)g[i];
     }
     double *delta = n->g2; /* o is no longer needed */
-    for (long i = 0; i < (long)S * l->out_size; ++i) delta[i] = opr(n, g[i] * dphi_at(n, l->act, l->z[i]));
+    for (long i = 0; i < (long)S * l->out_size; ++i) delta[i] = opr(n, g[i] * dphi(l->act, l->z[i]));
     if (l->act == A_RELU)
-      for (long i = 0; i < (long)S * l->out_size; ++i) {
-        if (g[i] == 0.0) continue;
-        const double az = fabs(l->z[i]);
-        if (az < n->kink_margin) n->kink_margin = az;
-        if (az < n->band_eps) {
-          if (n->n_events < n->cap_events) {
-            long *e = n->events + 3 * n->n_events;
-            e[0] = n->tick; e[1] = f + j; e[2] = i;
+      for (int s = 0; s < S; ++s) {
+        const double *us = l->u + s * l->in_size;
+        const double bound = n->band_eps > 0.0 ? n->band_eps * layer_abs_bound(l, us) : 0.0;
+        for (long q = 0; q < l->out_size; ++q) {
+          const long i = s * l->out_size + q;
+          if (g[i] == 0.0) continue;
+          const double az = fabs(l->z[i]);
+          if (az < n->kink_margin) n->kink_margin = az;
+          /* test band (see oracle_set_kink_band): |z| below band_eps times the size of the unit's terms */
+          if (az < bound && az < n->band_eps * unit_abs_sum(l, us, q)) {
+            if (n->n_events < n->cap_events) {
+              long *e = n->events + 3 * n->n_events;
+              e[0] = n->tick; e[1] = f + j; e[2] = i;
+            }
+            n->n_events += 1;
+            if (n->band_side != 0) delta[i] = opr(n, n->band_side > 0 ? g[i] : 0.0);
           }
-          n->n_events += 1;
         }
       }
     for (int s = 0; s < S; ++s)

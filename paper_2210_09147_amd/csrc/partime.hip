@@ -2384,6 +2384,7 @@ int partime_set_state(partime_ctx *ctx, int layer, const float *w_host, const fl
 
 static int buffer_args(partime_ctx *ctx, int which, int stage, int half, const void *host, const char *fn) {
   if (!ctx || !host) return fail(PT_EINVAL, "%s: null argument", fn);
+  if (which == 2) return PT_OK;   // the target history: stage and half are not used
   if (which < 0 || which > 1 || half < 0 || half > 1 || stage < 0 || stage >= ctx->depth)
     return fail(PT_EINVAL, "%s: which/stage/half out of range", fn);
   if (which == 0 && stage == ctx->depth - 1) return fail(PT_EINVAL, "%s: the last stage publishes no activation", fn);
@@ -2395,6 +2396,12 @@ int partime_get_buffer(partime_ctx *ctx, int which, int stage, int half, float *
   int rc = buffer_args(ctx, which, stage, half, host, "partime_get_buffer");
   if (rc != PT_OK) return rc;
   if ((rc = sync_and_check(ctx)) != PT_OK) return rc;
+  if (which == 2) {
+    // the last target_delay targets, oldest first, as the 4-byte elements the caller supplied them in
+    if (ctx->k > 0 && ctx->cfg.loss != PT_LOSS_NONE)
+      HIP_TRY(hipMemcpy(host, ctx->d_hist[ctx->hist_cur], (size_t)ctx->k * ctx->tgt_bytes, hipMemcpyDeviceToHost));
+    return PT_OK;
+  }
   if (ctx->cv) {
     // a stage's activation is its last layer's, its error its first layer's; the last stage is the head
     const int HW = ctx->cvs[0].H * ctx->cvs[0].W, fl = ctx->first_node[stage];
@@ -2468,6 +2475,11 @@ int partime_set_buffer(partime_ctx *ctx, int which, int stage, int half, const f
   int rc = buffer_args(ctx, which, stage, half, host, "partime_set_buffer");
   if (rc != PT_OK) return rc;
   HIP_TRY(hipStreamSynchronize(ctx->stream));
+  if (which == 2) {
+    if (ctx->k > 0 && ctx->cfg.loss != PT_LOSS_NONE)
+      HIP_TRY(hipMemcpy(ctx->d_hist[ctx->hist_cur], host, (size_t)ctx->k * ctx->tgt_bytes, hipMemcpyHostToDevice));
+    return PT_OK;
+  }
   if (ctx->cv) {
     const int HW = ctx->cvs[0].H * ctx->cvs[0].W, fl = ctx->first_node[stage];
     if (which == 0) {

@@ -196,6 +196,9 @@ def workload(cfg: int, ticks: Optional[int] = None) -> Workload:
 
 
 def small_mlp(widths, act=ACT_RELU, loss=LOSS_MSE, **kw) -> Workload:
+    """A small test network.  Its class targets are a noisy teacher: half of the labels are replaced by seeded random
+    classes, so that a short, fast-learning test run cannot drive the loss (and with it every error signal) to zero."""
+    kw.setdefault("extra", {"label_noise": 0.5} if loss == LOSS_CE else {})
     return Workload("mlp_" + "x".join(map(str, widths)), mlp(widths, act), loss=loss,
                     n_classes=widths[-1] if loss == LOSS_CE else 0, **kw)
 
@@ -311,6 +314,11 @@ def make_inputs(w: Workload, ticks: Optional[int] = None):
     x = smooth_stream(T, w.in_size, w.drift, w.seed, w.n_streams)
     if w.loss == LOSS_CE:
         tgt = teacher_classes(x, w.n_classes, w.seed)
+        noise = w.extra.get("label_noise", 0.0)
+        if noise > 0.0:
+            rng = np.random.Generator(np.random.PCG64(w.seed + 6000))
+            swap = rng.random(tgt.shape) < noise
+            tgt = np.where(swap, rng.integers(0, w.n_classes, size=tgt.shape), tgt).astype(np.int32)
     else:
         tgt = teacher_regression(x, w.out_size, w.seed)
     return x, tgt

@@ -1,7 +1,12 @@
 """GPU parity: the HIP path, called through the C ABI, against the CPU oracle on the same seeded inputs.
 
-Bars (stated by the build's goal): fp32 within 1e-5 relative, bf16-stored weights within 2e-2.
-Per-tick outputs and final weights are compared norm-wise (||a-b||/||b||), losses relatively.
+Bars (stated by the build's goal): fp32 within 1e-5, bf16-stored weights and bf16 matrix-core operands within 2e-2,
+applied element by element (relative to the largest element of the reference array) and in the 2-norm, to every
+output row, loss, published activation / error buffer, Adam moment and to the UPDATE of every weight and bias
+(W - W_before, not W).  Stored bf16 weights must also be bit-identical in all but 3 % of their elements and one bf16
+step apart in the rest.  How ReLU units within rounding distance of z = 0 are treated is described in parity.py.
+Every family and every full-size configuration has a negative control: a library that leaves the weights alone
+(step size 0 on the GPU side only) must FAIL the same comparison.
 """
 import numpy as np
 import pytest
@@ -10,73 +15,80 @@ import torch
 import oracle as orc
 import partime_streams as ps
 from paper_2210_09147_amd import Pipeline, binding as B
+from parity import BF16_TOL, F32_TOL, Pair, compare, Report
 
 pytestmark = pytest.mark.gpu
 
-F32_TOL, BF16_TOL = 1e-5, 2e-2
 CONV_TOL = 1e-5   # fp32 matrix-core sums (up to 576 terms, fp32, another order than the oracle's fp64)
-# ReLU's derivative jumps at z = 0 (Eq. 9 takes it at this tick's z).  When the oracle's fp64 z of some unit with a
-# non-zero error signal lies within the rounding error of an fp32 sum (a few 1e-7 for sums of some hundred terms
-# of magnitude <= 1), the kernel's fp32 z can land on the other side: both derivatives are valid choices at the
-# kink, the trajectories then differ by that one unit's contribution (~1e-5 .. 1e-4 in the weights), and there is
-# no unique element-wise answer.  Such runs are checked against KINK_TOL instead; all others against the strict bar.
-KINK_EPS, KINK_TOL = 5e-7, 1e-3
-
-
-def kink_aware(ref, tol):
-    margin = ref.take_kink_margin()
-    if margin < KINK_EPS and tol < KINK_TOL:
-        print(f"note: a ReLU derivative was taken at |z| = {margin:.1e}; tolerance {tol:g} -> {KINK_TOL:g}")
-        return KINK_TOL
-    return tol
 
 
 def rel(a, b):
-    return float(np.linalg.norm(np.asarray(a, np.float64) - b) / max(np.linalg.norm(b), 1e-30))
+    """The larger of the worst element error relative to the largest reference element and the 2-norm error."""
+    a, b = np.asarray(a, np.float64), np.asarray(b, np.float64)
+    return float(max(np.abs(a - b).max() / max(np.abs(b).max(), 1e-30), np.linalg.norm(a - b) / max(np.linalg.norm(b), 1e-30)))
 
 
-def run_pair(w, T, chunks=None, bf16=False, check_weights=True, tol=None, k=None, exec_mode=B.PT_EXEC_AUTO,
-             return_weights=False, adam=None):
-    tol = tol or (BF16_TOL if bf16 else F32_TOL)
-    k = w.k if k is None else k
-    Ws, bs = ps.init_weights(w.layers, w.seed)
-    x, tg = ps.make_inputs(w, T)
-    S = w.n_streams
-    ref = orc.Oracle(w.layers, Ws, bs, loss=w.loss, lr=w.lr, target_delay=k, w_bf16=bf16, n_streams=S,
-                     operands_bf16=S > 1, balance=w.balance, adam=adam)
-    ro, rl = ref.step(x, tg)
-    tol = kink_aware(ref, tol)
-    p = Pipeline(w.layers, Ws, bs, loss=w.loss, lr=w.lr, target_delay=k, w_dtype=B.PT_BF16 if bf16 else B.PT_F32,
-                 exec_mode=exec_mode, n_streams=S, balance=w.balance, adam=adam)
-    xd, td = torch.from_numpy(x).cuda(), torch.from_numpy(tg).cuda()
-    outs, losses = [], []
-    for i, j in chunks or [(0, T)]:
-        o, l = p.step(xd[i:j], td[i:j])
-        outs.append(o)
-        losses.append(l)
-    torch.cuda.synchronize()
-    out = torch.cat(outs).cpu().numpy()
-    loss = torch.cat(losses).cpu().numpy()
-    assert p.tick == T
-    D = w.depth
-    worst = max(rel(out[t], ro[t]) for t in range(D - 1, T))
-    assert worst < tol, f"output mismatch {worst}"
-    fill = max(D - 1, k)
-    assert np.all(loss[:fill] == 0)
-    lmax = max(abs(loss[t] - rl[t]) / max(abs(rl[t]), 1e-3) for t in range(T))
-    assert lmax < 10 * tol, f"loss mismatch {lmax}"
-    if check_weights:
-        for i in range(len(w.layers)):
-            W, b = p.weights(i)
-            W0, b0 = ref.get_weights(i)
-            assert rel(W, W0) < tol and rel(b, b0) < tol, f"layer {i}: {rel(W, W0)} {rel(b, b0)}"
-            if adam is not None:
-                for got, want in zip(p.moments(i), ref.get_moments(i)):
-                    assert rel(got, want) < tol, f"layer {i} moments: {rel(got, want)}"
-    B.partime_sync(p.ctx)
-    ws = [p.weights(i) for i in range(len(w.layers))] if return_weights else None
-    p.close()
-    return (out, loss, ws) if return_weights else (out, loss)
+def movement(pair):
+    """Per layer: largest change of a weight since the start, relative to the largest weight (oracle side)."""
+    out = []
+    for i in range(len(pair.layers)):
+        W = pair.ref.get_weights(i)[0].astype(np.float64)
+        out.append(float(np.abs(W - pair.Ws_stored[i]).max() / np.abs(pair.Ws_stored[i]).max()))
+    return out
+
+
+def run_pair(w, T, chunks=None, bf16=False, tol=None, k=None, exec_mode=B.PT_EXEC_AUTO, return_weights=False, adam=None,
+             pipes=None, x=None, tg=None, min_move=None, expect_blind=False, negative=False):
+    """T learning ticks on the oracle and on one or more library pipelines; every tick's output and loss, and the
+    updates, moments and published buffers are compared (see parity.py).  min_move: every layer must have moved by at
+    least this fraction of its largest weight, so that the update check cannot pass on weights that never change."""
+    pipes = pipes or [{"exec_mode": exec_mode, "chunks": chunks}]
+    has_skips = any(getattr(l, "skip_from", -1) >= 0 for l in w.layers)
+    if x is not None:
+        assert len(x) == T + 1
+    pair = Pair(w, bf16=bf16, k=k, adam=adam, tol=tol, pipes=pipes, T=T + 1, x=x, tg=tg)
+    pair.Ws_stored = [pair.ref.get_weights(i)[0].astype(np.float64) for i in range(len(w.layers))]
+    outs, losses = pair.run(0, T)
+    fill = max(pair.D - 1, pair.k)
+    for l in losses:
+        assert np.all(l[:fill] == 0)
+    if expect_blind:
+        return pair
+    if not has_skips:
+        # one more tick, taken from the oracle's state on both sides: everything at the full bar.  (Not for nets with
+        # skip connections: the delay lines of the skipped tensors cannot be handed over through the C ABI.)
+        # negative: under a step size that lifts every layer's update well above the storage rounding of its weights,
+        # and first with a library that does not update at all, which must fail for every layer
+        big = 0.1 if (bf16 or w.n_streams > 1) else 0.02
+        pair.forced_tick(T, lr=pair.pick_lr(big) if negative else None, negative=negative)
+    else:
+        assert not negative, "use assert_sees_updates for nets with skip connections"
+    pair.assert_ok()
+    if min_move is not None:
+        mv = movement(pair)
+        assert min(mv) >= min_move, f"weights barely move ({mv}): the update check would be blind"
+    ws = [[p.weights(i) for i in range(len(w.layers))] for p in pair.pipes] if return_weights else None
+    pair.close()
+    # pipelines that differ only in execution mode or in how the ticks were split over calls must agree bit by bit
+    for o, l in zip(outs[1:], losses[1:]):
+        assert np.array_equal(outs[0], o) and np.array_equal(losses[0], l)
+    if return_weights:
+        for other in ws[1:]:
+            for (W1, b1), (W2, b2) in zip(ws[0], other):
+                assert np.array_equal(W1, W2) and np.array_equal(b1, b2)
+        return outs[0], losses[0], ws[0]
+    return outs[0], losses[0]
+
+
+def assert_sees_updates(w, T, **kw):
+    """Negative control for nets with skip connections (the others end run_pair with a forced tick that carries it): the
+    same free run with a library that never updates (step size 0 on the GPU side only) must fail the update comparison
+    for every layer."""
+    pair = run_pair(w, T, pipes=[{"gpu_lr": 0.0}], expect_blind=True, **kw)
+    for i in range(len(w.layers)):
+        hits = [f for f in pair.rep.failures if f" update of W{i}" in f]
+        assert hits, f"a library that never updates layer {i} passes: the comparison is blind there"
+    pair.close()
 
 
 @pytest.mark.parametrize("act", [ps.ACT_RELU, ps.ACT_GELU])
@@ -84,7 +96,7 @@ def run_pair(w, T, chunks=None, bf16=False, check_weights=True, tol=None, k=None
 def test_small_ragged_mlp_fp32(act, loss):
     # sizes that are not multiples of the vector width, of a wave, or of the rows a wave takes at once
     w = ps.small_mlp([97, 131, 70, 257, 11], act, loss, lr=0.02, drift=0.05, seed=1)
-    run_pair(w, 60)
+    run_pair(w, 60, min_move=1e-3, negative=act == ps.ACT_RELU)
 
 
 def test_single_stage_and_two_stage():
@@ -106,21 +118,18 @@ def test_target_delay_zero_and_large():
 
 
 def test_chunked_calls_match_one_call_bitwise():
+    # two pipelines against one oracle pass; run_pair asserts that they agree bit by bit
     w = ps.small_mlp([48, 64, 64, 7], ps.ACT_GELU, ps.LOSS_CE, lr=0.05, drift=0.05, seed=6)
-    a = run_pair(w, 40)
-    b = run_pair(w, 40, chunks=[(0, 1), (1, 2), (2, 3), (3, 17), (17, 40)])
-    assert np.array_equal(a[0], b[0]) and np.array_equal(a[1], b[1])
+    run_pair(w, 40, pipes=[{}, {"chunks": [(0, 1), (1, 2), (2, 3), (3, 17), (17, 40)]}], return_weights=True)
     w2 = ps.small_mlp([48, 64, 64, 9], ps.ACT_RELU, ps.LOSS_MSE, lr=0.05, drift=0.05, seed=6, target_delay=4)
-    a = run_pair(w2, 40)
-    b = run_pair(w2, 40, chunks=[(0, 1), (1, 3), (3, 4), (4, 30), (30, 40)])
-    assert np.array_equal(a[0], b[0]) and np.array_equal(a[1], b[1])
+    run_pair(w2, 40, pipes=[{}, {"chunks": [(0, 1), (1, 3), (3, 4), (4, 30), (30, 40)]}], return_weights=True)
 
 
 def test_wide_rows_all_register_layouts_fp32():
     # in_dim 256..4096 exercises every rows-in-registers variant; out_dim leaves a ragged last tile
     for d in (256, 512, 1024, 2048, 4096):
-        w = ps.small_mlp([d, 200, d, 37], ps.ACT_RELU, ps.LOSS_MSE, lr=1e-3, drift=0.02, seed=d)
-        run_pair(w, 10)
+        w = ps.small_mlp([d, 200, d, 37], ps.ACT_RELU, ps.LOSS_MSE, lr=0.02, drift=0.02, seed=d)
+        run_pair(w, 12, min_move=1e-3)
 
 
 def test_bf16_weights():
@@ -146,37 +155,18 @@ def test_inference_only_matches_and_keeps_weights():
 
 
 def test_single_tick_from_oracle_state():
-    """Load the oracle's state mid-run into the library, run one tick on both, compare everything."""
+    """The oracle's state mid-run handed to the library (weights, both halves of every buffer, target history, tick),
+    then one tick on both: output, loss, updates and the published buffers element by element; the second tick
+    uses a step size under which every layer's update is a few per cent of its weights, and a library that does
+    not update must fail it."""
     w = ps.small_mlp([120, 200, 96, 140, 10], ps.ACT_RELU, ps.LOSS_MSE, lr=0.02, drift=0.05, seed=9)
-    D = w.depth
-    Ws, bs = ps.init_weights(w.layers, w.seed)
-    x, tg = ps.make_inputs(w, 31)
-    ref = orc.Oracle(w.layers, Ws, bs, loss=w.loss, lr=w.lr, target_delay=0)
-    ref.step(x[:30], tg[:30])
-    p = Pipeline(w.layers, Ws, bs, loss=w.loss, lr=w.lr, target_delay=0)
-    for i in range(D):
-        W, b = ref.get_weights(i)
-        p.set_weights(i, W, b)
-    for h in range(D):
-        for half in (0, 1):
-            if h < D - 1:
-                B.partime_set_buffer(p.ctx, 0, h, half, ref.get_buffer("act", h, half))
-            if h > 0:
-                B.partime_set_buffer(p.ctx, 1, h, half, ref.get_buffer("err", h, half))
-    B.partime_set_tick(p.ctx, 30)
-    ro, rl = ref.step(x[30:], tg[30:])
-    out, loss = p.step(torch.from_numpy(x[30:]).cuda(), torch.from_numpy(tg[30:]).cuda())
-    assert rel(out.cpu().numpy()[0], ro[0]) < 2e-6
-    assert abs(loss.item() - rl[0]) / rl[0] < 1e-5
-    for h in range(D):
-        W, b = p.weights(h)
-        W0, b0 = ref.get_weights(h)
-        assert rel(W, W0) < 1e-6 and rel(b, b0) < 1e-6
-        if h < D - 1:
-            assert rel(B.partime_get_buffer(p.ctx, 0, h, 0, w.layers[h].out_dim), ref.get_buffer("act", h, 0)[0]) < 2e-6
-        if h > 0:
-            assert rel(B.partime_get_buffer(p.ctx, 1, h, 0, w.layers[h].in_dim), ref.get_buffer("err", h, 0)[0]) < 1e-5
-    p.close()
+    pair = Pair(w, T=34)
+    pair.warm(0, 30)
+    pair.forced_tick(30)
+    pair.forced_tick(31, lr=pair.pick_lr(0.05), negative=True)
+    pair.run(32, 34)                 # and on from there, freely
+    pair.assert_ok()
+    pair.close()
 
 
 def test_zero_ticks_reset_and_errors():
@@ -202,20 +192,55 @@ def test_zero_ticks_reset_and_errors():
 
 def test_config0_full_trajectory():
     w = ps.workload(0)
-    out, loss = run_pair(w, w.ticks)
+    out, loss = run_pair(w, w.ticks, min_move=1e-3)
     assert np.isfinite(out).all()
 
 
-def test_config1_full_size_short_run():
-    """The benchmark workload (8 x 4096 x 4096 fp32) at full size, in the launch configuration bench.py
-    times, for a few ticks past the pipeline fill; every output element is compared."""
+def full_size_forced(w, warm_ticks, *, bf16=False, adam=None, tol=None, rel_step=0.02, synthetic=False, free=0,
+                     err_scale=1e-3, n_forced=2):
+    """A full-size workload in the launch configuration bench.py times: the oracle runs `warm_ticks` ticks (or starts
+    from a synthetic full pipeline where a plain-loop warm-up would take minutes), then two consecutive ticks (both
+    ping-pong halves, both row directions) are taken from the oracle's state on both sides under a step size that
+    moves every layer by a few per cent, the first one with the negative control; `free` further ticks run freely."""
+    pair = Pair(w, bf16=bf16, adam=adam, tol=tol, T=warm_ticks + n_forced + free)
+    if synthetic and adam is not None:
+        pair.synthetic_state(warm_ticks, seed=w.seed, err_scale=err_scale)     # (an Adam step needs no gradient to be sized)
+    elif synthetic:
+        pair.synthetic_state(warm_ticks - 1, seed=w.seed, err_scale=err_scale)
+        pair.warm(warm_ticks - 1, warm_ticks)                                 # one tick for the gradients pick_lr looks at
+    else:
+        pair.warm(0, warm_ticks)
+    lr = pair.pick_lr(rel_step)
+    pair.forced_tick(warm_ticks, lr=lr, negative=True)
+    if n_forced > 1:
+        pair.forced_tick(warm_ticks + 1, lr=lr)
+    if free:
+        pair.run(warm_ticks + n_forced, warm_ticks + n_forced + free)
+    pair.assert_ok()
+    print(f"{w.name}: {len(pair.rep.rows)} arrays compared, worst {pair.rep.worst():.3f} x tol, "
+          f"{pair.rep.events} undecided ReLU units in {pair.rep.event_ticks} ticks, largest |z - z_oracle| seen {pair.rep.z_err:.2e}")
+    pair.close()
+
+
+def test_config1_full_size():
+    """The benchmark workload (8 x 4096 x 4096 fp32, ReLU, MSE) at full size: 2 D + 2 oracle ticks fill the pipeline
+    and bring a real error signal to every stage, then two checked ticks and two free ones."""
     w = ps.workload(1)
-    run_pair(w, 20)
+    full_size_forced(w, 2 * w.depth + 2, free=2)
 
 
-def test_config2_full_size_short_run_bf16():
+def test_config2_full_size_bf16():
+    """16 x 2048 bf16 GELU, CE: a free run past the fill (no ReLU: the whole trajectory is unique), then two checked
+    ticks whose step size lifts every layer's update above the bf16 spacing of its weights."""
     w = ps.workload(2)
-    run_pair(w, 36, bf16=True)
+    T0 = 2 * w.depth + 2
+    pair = Pair(w, T=T0 + 2)
+    pair.run(0, T0)
+    lr = pair.pick_lr(0.1)
+    pair.forced_tick(T0, lr=lr, negative=True)
+    pair.forced_tick(T0 + 1, lr=lr)
+    pair.assert_ok()
+    pair.close()
 
 
 # ----------------------------------------------------------------------------- persistent multi-tick kernel
@@ -226,29 +251,45 @@ PERSIST_CASES = [
     (lambda: ps.small_mlp([33, 5], ps.ACT_ID, ps.LOSS_MSE, lr=0.05, drift=0.05, seed=2), 30, False),
     (lambda: ps.small_mlp([130, 257, 96, 12], ps.ACT_GELU, ps.LOSS_CE, lr=0.05, drift=0.05, seed=7), 50, True),
     (lambda: ps.workload(0), 1000, False),
-    (lambda: ps.workload(1), 12, False),
-    (lambda: ps.workload(2), 36, True),
 ]
+TWO_MODES = [{"exec_mode": B.PT_EXEC_LAUNCH_PER_TICK}, {"exec_mode": B.PT_EXEC_PERSISTENT}]
 
 
 @pytest.mark.parametrize("case", range(len(PERSIST_CASES)))
 def test_persistent_kernel_matches_oracle_and_launch_per_tick_bitwise(case):
     """One launch for a block of ticks with a grid barrier between ticks: same arithmetic in the same order as
     one launch per tick, so every output, loss and weight must be bit-identical (a stale read across the
-    barrier would show here), and both must match the oracle."""
+    barrier would show here), and both must match the oracle (one oracle pass drives both pipelines)."""
     mk, T, bf16 = PERSIST_CASES[case]
-    a = run_pair(mk(), T, bf16=bf16, exec_mode=B.PT_EXEC_LAUNCH_PER_TICK, return_weights=True)
-    b = run_pair(mk(), T, bf16=bf16, exec_mode=B.PT_EXEC_PERSISTENT, return_weights=True)
-    assert np.array_equal(a[0], b[0]) and np.array_equal(a[1], b[1])
-    for (W1, b1), (W2, b2) in zip(a[2], b[2]):
+    run_pair(mk(), T, bf16=bf16, pipes=TWO_MODES, return_weights=True)
+
+
+@pytest.mark.parametrize("cfg,T,bf16", [(1, 24, False), (2, 36, True)])
+def test_persistent_kernel_full_size_bitwise(cfg, T, bf16):
+    """The two execution modes at full size (8 x 4096 fp32, 16 x 2048 bf16), bit by bit against each other over a run
+    past the fill; the launch-per-tick mode is the one the full-size configuration tests compare with the oracle."""
+    w = ps.workload(cfg)
+    w.lr *= 100.0                    # every stage's weights change within the run
+    Ws, bs = ps.init_weights(w.layers, w.seed)
+    x, tg = ps.make_inputs(w, T)
+    xd, td = torch.from_numpy(x).cuda(), torch.from_numpy(tg).cuda()
+    res = []
+    for kw in TWO_MODES:
+        p = Pipeline(w.layers, Ws, bs, loss=w.loss, lr=w.lr, target_delay=w.k, w_dtype=B.PT_BF16 if bf16 else B.PT_F32, **kw)
+        o, l = p.step(xd, td)
+        res.append((o.cpu().numpy(), l.cpu().numpy(), [p.weights(i) for i in range(len(w.layers))]))
+        B.partime_sync(p.ctx)
+        p.close()
+    assert np.array_equal(res[0][0], res[1][0]) and np.array_equal(res[0][1], res[1][1])
+    for (W1, b1), (W2, b2) in zip(res[0][2], res[1][2]):
         assert np.array_equal(W1, W2) and np.array_equal(b1, b2)
+    assert np.isfinite(res[0][0]).all()
 
 
 def test_persistent_chunked_and_infer():
     w = ps.small_mlp([48, 64, 64, 7], ps.ACT_GELU, ps.LOSS_CE, lr=0.05, drift=0.05, seed=6, target_delay=3)
-    a = run_pair(w, 40, exec_mode=B.PT_EXEC_PERSISTENT)
-    b = run_pair(w, 40, exec_mode=B.PT_EXEC_PERSISTENT, chunks=[(0, 1), (1, 3), (3, 4), (4, 30), (30, 40)])
-    assert np.array_equal(a[0], b[0]) and np.array_equal(a[1], b[1])
+    run_pair(w, 40, pipes=[{"exec_mode": B.PT_EXEC_PERSISTENT},
+                           {"exec_mode": B.PT_EXEC_PERSISTENT, "chunks": [(0, 1), (1, 3), (3, 4), (4, 30), (30, 40)]}])
     Ws, bs = ps.init_weights(w.layers, w.seed)
     x, _ = ps.make_inputs(w, 25)
     xd = torch.from_numpy(x).cuda()
@@ -274,21 +315,26 @@ def ms_workload(widths, act, loss, **kw):
 def test_multistream_small_ragged(loss):
     # 32 streams sharing bf16 weights; sizes that are not multiples of the 16/32/64/128 blockings
     w = ms_workload([100, 130, 200, 70, 12], ps.ACT_RELU, loss, lr=0.05, drift=0.05, seed=3)
-    run_pair(w, 40, bf16=True)
-    w = ms_workload([64, 1100, 40], ps.ACT_GELU, loss, lr=0.05, drift=0.05, seed=4)   # more than one 1024-row tile
-    run_pair(w, 20, bf16=True)
+    run_pair(w, 40, bf16=True, min_move=2e-2, negative=True)
+    w = ms_workload([64, 1100, 40], ps.ACT_GELU, loss, lr=0.05, drift=0.05, seed=4)   # several forward tiles, one ragged
+    run_pair(w, 20, bf16=True, min_move=2e-2)
 
 
 def test_multistream_depth8_medium():
     w = ms_workload([512] * 8 + [100], ps.ACT_RELU, ps.LOSS_CE, lr=0.01, drift=0.02, seed=5)
-    run_pair(w, 40, bf16=True)
+    pair = Pair(w, T=28)
+    pair.run(0, 24)                                  # 2 D + 8 ticks: a real error signal has reached the first stage
+    lr = pair.pick_lr(0.1)
+    pair.forced_tick(24, lr=lr, negative=True)
+    pair.forced_tick(25, lr=lr)
+    pair.run(26, 28)
+    pair.assert_ok()
+    pair.close()
 
 
 def test_multistream_chunked_infer_and_state():
     w = ms_workload([96, 160, 80, 10], ps.ACT_RELU, ps.LOSS_CE, lr=0.05, drift=0.05, seed=6, target_delay=2)
-    a = run_pair(w, 30, bf16=True)
-    b = run_pair(w, 30, bf16=True, chunks=[(0, 1), (1, 2), (2, 11), (11, 30)])
-    assert np.array_equal(a[0], b[0]) and np.array_equal(a[1], b[1])
+    run_pair(w, 30, bf16=True, pipes=[{}, {"chunks": [(0, 1), (1, 2), (2, 11), (11, 30)]}], return_weights=True)
     Ws, bs = ps.init_weights(w.layers, w.seed)
     x, tg = ps.make_inputs(w, 12)
     ref = orc.Oracle(w.layers, Ws, bs, loss=w.loss, lr=w.lr, n_streams=32, w_bf16=True, operands_bf16=True)
@@ -309,14 +355,15 @@ def test_multistream_adam(loss):
     # 32 streams with Adam: moments of the weights (updated in the backward launch) and of the biases (forward epilogue,
     # loss head) against the oracle's
     w = ms_workload([100, 130, 600, 70, 12], ps.ACT_GELU, loss, lr=2e-3, drift=0.05, seed=13, target_delay=2)
-    run_pair(w, 24, bf16=True, adam=(0.9, 0.999, 1e-8))
-    run_pair(w, 24, bf16=True, adam=(0.9, 0.999, 1e-8), chunks=[(0, 3), (3, 4), (4, 24)])
+    run_pair(w, 24, bf16=True, adam=(0.9, 0.999, 1e-8), pipes=[{}, {"chunks": [(0, 3), (3, 4), (4, 24)]}], return_weights=True,
+             min_move=2e-2, negative=True)
 
 
-def test_config4_full_size_short_run_multistream():
-    """8 x 4096-wide bf16 layers (last 4096 -> 1000), 32 streams: the full-size shapes, a few ticks past the fill."""
+def test_config4_full_size_multistream():
+    """8 x 4096-wide bf16 layers (last 4096 -> 1000), 32 streams, at full size.  A tick of the plain-loop oracle is
+    about 25 GFLOP here, so the pipeline is not filled tick by tick: it starts from a synthetic full state."""
     w = ps.workload(4)
-    run_pair(w, 10, bf16=True)
+    full_size_forced(w, w.depth + 1, bf16=True, synthetic=True, rel_step=0.1)
 
 
 # ----------------------------------------------------------------------------- replay batch: 64 and more streams
@@ -340,20 +387,18 @@ def stream_tile(request, monkeypatch):
 def test_batched_sgd(S, loss, stream_tile):
     # sizes that are not multiples of the 128-wide tiles; 64 and 192 streams always take the 64-wide stream tiles
     w = batched_workload([100, 300, 130, 12], ps.ACT_RELU, loss, S, lr=0.05, drift=0.05, seed=3)
-    run_pair(w, 16, bf16=True)
+    run_pair(w, 16, bf16=True, min_move=1e-2, negative=S == 128)
 
 
 @pytest.mark.parametrize("S", [64, 256])
 def test_batched_adam_gelu(S, stream_tile):
     w = batched_workload([96, 260, 140, 10], ps.ACT_GELU, ps.LOSS_CE, S, lr=2e-3, drift=0.05, seed=4, target_delay=2)
-    run_pair(w, 14, bf16=True, adam=(0.9, 0.999, 1e-8))
+    run_pair(w, 14, bf16=True, adam=(0.9, 0.999, 1e-8), min_move=2e-2, negative=S == 64)
 
 
 def test_batched_chunked_and_infer():
     w = batched_workload([96, 160, 80, 10], ps.ACT_RELU, ps.LOSS_CE, 64, lr=0.05, drift=0.05, seed=6, target_delay=2)
-    a = run_pair(w, 14, bf16=True)
-    b = run_pair(w, 14, bf16=True, chunks=[(0, 1), (1, 2), (2, 9), (9, 14)])
-    assert np.array_equal(a[0], b[0]) and np.array_equal(a[1], b[1])
+    run_pair(w, 14, bf16=True, pipes=[{}, {"chunks": [(0, 1), (1, 2), (2, 9), (9, 14)]}], return_weights=True)
     Ws, bs = ps.init_weights(w.layers, w.seed)
     x, tg = ps.make_inputs(w, 8)
     ref = orc.Oracle(w.layers, Ws, bs, loss=w.loss, lr=w.lr, n_streams=64, w_bf16=True, operands_bf16=True)
@@ -377,7 +422,7 @@ def test_batched_full_width_short_run(monkeypatch):
     monkeypatch.setenv("PARTIME_RB_TN", "128")   # the tile width of the 8-stage benchmark configuration
     w = ps.workload(12)
     w.layers = ps.mlp([4096, 4096, 4096, 1000], ps.ACT_RELU)
-    run_pair(w, 6, bf16=True, adam=w.adam)
+    full_size_forced(w, w.depth + 1, bf16=True, adam=w.adam, synthetic=True, rel_step=0.1, n_forced=1)
 
 
 @pytest.mark.parametrize("balance", [[5], [2, 3], [3, 1, 1], [1, 2, 2]])
@@ -472,49 +517,23 @@ def test_batched_single_stage_and_state_round_trip():
 
 
 def test_batched_single_tick_from_oracle_state(stream_tile):
-    """The oracle's state after 11 ticks (weights, moments, both halves of every inter-stage buffer, tick) loaded into a
-    fresh pipeline of 128 streams: the next tick must agree on output, loss, weights and the buffers it writes."""
+    """The oracle's state after 11 ticks (weights, moments, both halves of every inter-stage buffer, tick) handed to a
+    pipeline of 128 streams: the next ticks must agree on output, loss, updates, moments and the buffers they write."""
     adam = (0.9, 0.999, 1e-8)
     w = batched_workload([100, 200, 130, 10], ps.ACT_GELU, ps.LOSS_CE, 128, lr=2e-3, drift=0.05, seed=14, target_delay=0)
-    D, S = w.depth, 128
-    Ws, bs = ps.init_weights(w.layers, w.seed)
-    x, tg = ps.make_inputs(w, 12)
-    ref = orc.Oracle(w.layers, Ws, bs, loss=w.loss, lr=w.lr, target_delay=0, w_bf16=True, n_streams=S, operands_bf16=True, adam=adam)
-    ref.step(x[:11], tg[:11])
-    p = Pipeline(w.layers, Ws, bs, loss=w.loss, lr=w.lr, target_delay=0, n_streams=S, w_dtype=B.PT_BF16, adam=adam)
-    for i in range(D):
-        W, b = ref.get_weights(i)
-        B.partime_set_state(p.ctx, i, W, b)
-        B.partime_set_opt_state(p.ctx, i, *ref.get_moments(i))
-    for h in range(D):
-        for half in (0, 1):
-            if h < D - 1:
-                B.partime_set_buffer(p.ctx, 0, h, half, ref.get_buffer("act", h, half))
-            if h > 0:
-                B.partime_set_buffer(p.ctx, 1, h, half, ref.get_buffer("err", h, half))
-    B.partime_set_tick(p.ctx, 11)
-    ro, rl = ref.step(x[11:], tg[11:])
-    out, loss = p.step(torch.from_numpy(x[11:]).cuda(), torch.from_numpy(tg[11:]).cuda())
-    assert rel(out.cpu().numpy()[0], ro[0]) < BF16_TOL
-    assert abs(loss.item() - rl[0]) / rl[0] < 10 * BF16_TOL
-    cur = 11 & 1
-    for h in range(D):
-        W, b = p.weights(h)
-        W0, b0 = ref.get_weights(h)
-        assert rel(W, W0) < BF16_TOL and rel(b, b0) < BF16_TOL
-        if h < D - 1:
-            got = B.partime_get_buffer(p.ctx, 0, h, cur, S * w.layers[h].out_dim).reshape(S, -1)
-            assert rel(got, ref.get_buffer("act", h, cur)) < BF16_TOL
-        if h > 0:
-            got = B.partime_get_buffer(p.ctx, 1, h, cur, S * w.layers[h].in_dim).reshape(S, -1)
-            assert rel(got, ref.get_buffer("err", h, cur)) < BF16_TOL
-    p.close()
+    pair = Pair(w, adam=adam, T=14)
+    pair.warm(0, 11)
+    pair.forced_tick(11)
+    pair.forced_tick(12, lr=pair.pick_lr(0.1), negative=True)
+    pair.run(13, 14)
+    pair.assert_ok()
+    pair.close()
 
 
 def test_batched_benchmark_configuration_short_run():
     """Workload 14 as bench.py runs it: all 8 stages at full width, replay batch of 64, Adam; a few ticks past the fill."""
     w = ps.workload(14)
-    run_pair(w, 10, bf16=True, adam=w.adam)
+    full_size_forced(w, w.depth + 1, bf16=True, adam=w.adam, synthetic=True, rel_step=0.1, n_forced=1)
 
 
 def test_batched_wide_layers(monkeypatch):
@@ -539,22 +558,11 @@ def test_conv_pipeline_small(shape, loss):
     if c_in != 3:
         wl.layers[0].c_in = c_in
     if c_in == 3:
-        run_pair(wl, 16, tol=CONV_TOL)
+        run_pair(wl, 16, tol=CONV_TOL, min_move=1e-4, negative=shape[1] == 32)
     else:   # a generic smooth stream for the odd channel count
-        Ws, bs = ps.init_weights(wl.layers, wl.seed)
-        x = ps.smooth_stream(14, c_in * h * w, 0.05, 1)
+        x = ps.smooth_stream(15, c_in * h * w, 0.05, 1)
         tg = ps.teacher_classes(x[:, :, :64], 6, 1) if loss == ps.LOSS_CE else ps.teacher_regression(x[:, :, :64], 6, 1)
-        ref = orc.Oracle(wl.layers, Ws, bs, loss=loss, lr=wl.lr, target_delay=wl.k)
-        ro, rl = ref.step(x, tg)
-        tol = kink_aware(ref, CONV_TOL)
-        p = Pipeline(wl.layers, Ws, bs, loss=loss, lr=wl.lr, target_delay=wl.k)
-        o, l = p.step(torch.from_numpy(x).cuda(), torch.from_numpy(tg).cuda())
-        o, l = o.cpu().numpy(), l.cpu().numpy()
-        assert max(rel(o[t], ro[t]) for t in range(wl.depth - 1, 14)) < tol
-        assert max(abs(l[t] - rl[t]) / max(abs(rl[t]), 1e-3) for t in range(14)) < 10 * tol
-        for i in range(len(wl.layers)):
-            assert rel(p.weights(i)[0], ref.get_weights(i)[0]) < tol
-        p.close()
+        run_pair(wl, 14, tol=CONV_TOL, x=x, tg=tg, min_move=2e-4)
 
 
 @pytest.mark.parametrize("balance", [None, [2, 1, 1]])
@@ -563,14 +571,12 @@ def test_conv_pipeline_adam(balance, loss):
     """Adam on conv kernels, biases and the pooled head (Sec. V-D trains a conv net with it); moments compared too."""
     wl = conv_workload(3, 32, 32, 3, 6, loss=loss, lr=1e-3, seed=5)
     wl.balance = balance
-    run_pair(wl, 14, tol=CONV_TOL, adam=ADAM)
+    run_pair(wl, 14, tol=CONV_TOL, adam=ADAM, min_move=2e-4, negative=balance is None)
 
 
 def test_conv_infer_chunks_and_state():
     wl = conv_workload(3, 32, 32, 2, 5, lr=0.05, seed=4, target_delay=1)
-    a = run_pair(wl, 12, tol=CONV_TOL)
-    b = run_pair(wl, 12, tol=CONV_TOL, chunks=[(0, 1), (1, 5), (5, 12)])
-    assert np.array_equal(a[0], b[0]) and np.array_equal(a[1], b[1])
+    run_pair(wl, 12, tol=CONV_TOL, pipes=[{}, {"chunks": [(0, 1), (1, 5), (5, 12)]}], return_weights=True)
     Ws, bs = ps.init_weights(wl.layers, wl.seed)
     x, _ = ps.make_inputs(wl, 8)
     ref = orc.Oracle(wl.layers, Ws, bs, loss=wl.loss, lr=wl.lr)
@@ -585,10 +591,11 @@ def test_conv_infer_chunks_and_state():
     p.close()
 
 
-def test_config3_full_size_short_run_conv():
-    """8 conv3x3(64) stages at 128 x 128 + pooled head, depth 9: full-size shapes, a few ticks past the fill."""
+def test_config3_full_size_conv():
+    """8 conv3x3(64) stages at 128 x 128 + pooled head, depth 9, at full size, from a synthetic full pipeline (a tick of
+    the plain-loop oracle is 25 GFLOP): forward, backward-data, weight gradient and update of every stage."""
     wl = ps.workload(3)
-    run_pair(wl, 12, tol=CONV_TOL)
+    full_size_forced(wl, wl.depth + 1, tol=CONV_TOL, synthetic=True, rel_step=0.05)
 
 
 # ----------------------------------------------------------------------------- several layers per stage (Eq. 3-5)
@@ -601,7 +608,7 @@ def test_several_layers_per_stage_fp32(balance, loss):
     widths = [97, 131, 70, 257, 64, 33, 150, 11][:n] + [13]
     w = ps.small_mlp(widths, ps.ACT_GELU, loss, lr=0.02, drift=0.05, seed=11, balance=balance)
     assert w.depth == len(balance)
-    run_pair(w, 40)
+    run_pair(w, 40, min_move=5e-4, negative=balance == [1, 3, 2])
     run_pair(w, 40, chunks=[(0, 1), (1, 2), (2, 17), (17, 40)], k=0)
 
 
@@ -641,10 +648,10 @@ def test_several_layers_per_stage_stage_buffers_and_launch_count():
     p.close()
 
 
-def test_two_layers_per_stage_full_size_short_run():
+def test_two_layers_per_stage_full_size():
     """The 8 x 4096 fp32 network in 4 stages of two layers: full-size shapes in the launch configuration of the bench."""
     w = ps.workload(5)
-    run_pair(w, 10, check_weights=True)
+    full_size_forced(w, 2 * w.depth + 2)
 
 
 def test_persistent_barrier_timeout_is_reported_not_hung(monkeypatch):
@@ -678,8 +685,8 @@ ADAM = (0.9, 0.999, 1e-8)
 def test_adam_small_ragged_fp32(loss, balance):
     # GELU keeps the comparison free of kink decisions
     w = ps.small_mlp([97, 131, 70, 257, 11], ps.ACT_GELU, loss, lr=1e-3, drift=0.05, seed=21, balance=balance)
-    run_pair(w, 40, adam=ADAM)
-    run_pair(w, 40, adam=ADAM, chunks=[(0, 3), (3, 4), (4, 40)])
+    run_pair(w, 40, adam=ADAM, pipes=[{}, {"chunks": [(0, 3), (3, 4), (4, 40)]}], return_weights=True, min_move=1e-3,
+             negative=balance is None)
 
 
 def test_adam_wide_rows_bf16_and_single_tick():
@@ -688,35 +695,23 @@ def test_adam_wide_rows_bf16_and_single_tick():
         run_pair(w, 12, adam=ADAM)
     w = ps.small_mlp([300, 500, 260, 9], ps.ACT_RELU, ps.LOSS_CE, lr=1e-3, drift=0.05, seed=22)
     run_pair(w, 30, adam=ADAM, bf16=True)
-    # one tick from identical state (weights and moments from the oracle after 20 ticks): rounding only
+    # ticks from the oracle's state (weights, moments, buffers, target history after 20 ticks)
+    pair = Pair(w, adam=ADAM, T=23)
+    pair.warm(0, 20)
+    pair.forced_tick(20)
+    pair.forced_tick(21, lr=pair.pick_lr(0.05), negative=True)
+    pair.run(22, 23)
+    pair.assert_ok()
+    pair.close()
     Ws, bs = ps.init_weights(w.layers, w.seed)
-    x, tg = ps.make_inputs(w, 21)
-    ref = orc.Oracle(w.layers, Ws, bs, loss=w.loss, lr=w.lr, adam=ADAM)
-    ref.step(x[:20], tg[:20])
-    p = Pipeline(w.layers, Ws, bs, loss=w.loss, lr=w.lr, adam=ADAM)
-    for i in range(3):
-        p.set_weights(i, *ref.get_weights(i))
-        B.partime_set_opt_state(p.ctx, i, *ref.get_moments(i))
-    for h in range(2):
-        for half in (0, 1):
-            B.partime_set_buffer(p.ctx, 0, h, half, ref.get_buffer("act", h, half)[0])
-            B.partime_set_buffer(p.ctx, 1, h + 1, half, ref.get_buffer("err", h + 1, half)[0])
-    B.partime_set_tick(p.ctx, 20)
-    ref.step(x[20:], tg[20:])
-    p.step(torch.from_numpy(x[20:]).cuda(), torch.from_numpy(tg[20:]).cuda())
-    for i in range(3):
-        assert rel(p.weights(i)[0], ref.get_weights(i)[0]) < 1e-6
-        for got, want in zip(p.moments(i), ref.get_moments(i)):
-            assert rel(got, want) < 1e-5
     with pytest.raises(B.PartimeError):
         Pipeline(w.layers, Ws, bs, loss=w.loss, lr=w.lr, adam=ADAM, exec_mode=B.PT_EXEC_PERSISTENT)
-    p.close()
 
 
-def test_adam_full_size_short_run():
+def test_adam_full_size():
     """The 8 x 4096 fp32 network under Adam: full-size shapes in the launch configuration of the bench."""
     w = ps.workload(6)
-    run_pair(w, 12, adam=w.adam)
+    full_size_forced(w, 2 * w.depth + 2, adam=w.adam)
 
 
 # ----------------------------------------------------------------------------- several conv layers per stage
@@ -730,9 +725,9 @@ def test_conv_several_layers_per_stage(balance, act):
         l.act = act
     wl.balance = balance
     assert wl.depth == len(balance)
-    run_pair(wl, 14, tol=CONV_TOL)
+    run_pair(wl, 14, tol=CONV_TOL, min_move=2e-4)
     if balance == [2, 2, 1]:
-        a = run_pair(wl, 12, tol=CONV_TOL, chunks=[(0, 1), (1, 5), (5, 12)], k=0)
+        run_pair(wl, 12, tol=CONV_TOL, chunks=[(0, 1), (1, 5), (5, 12)], k=0, negative=True)
         # forward-only ticks on the same pipeline shape
         Ws, bs = ps.init_weights(wl.layers, wl.seed)
         x, _ = ps.make_inputs(wl, 8)
@@ -768,6 +763,26 @@ def test_conv_other_feature_map_counts(feat):
     p.close()
 
 
+@pytest.mark.parametrize("feat,h,act,adam", [(64, 8, ps.ACT_RELU, None), (64, 4, ps.ACT_GELU, (0.9, 0.999, 1e-8)), (1, 16, ps.ACT_GELU, None),
+                                             (10, 8, ps.ACT_RELU, (0.9, 0.999, 1e-8)), (100, 4, ps.ACT_GELU, None)])
+def test_conv_frames_256_wide(feat, h, act, adam):
+    """The kernel instantiation the 150-layer stack of Sec. V-A runs on (256-wide frames: one row of 256 pixels per tile,
+    the 64-column weight-gradient variant), with the feature-map counts of Table 1 and three layers per stage: a free run
+    past the fill, a forced tick with the negative control, and forward-only ticks."""
+    ls = ps.conv_net(3, h, 256, 6, 5, act=act, feat=feat)
+    wl = ps.Workload(f"cnn6_f{feat}_{h}x256", ls, loss=ps.LOSS_CE, n_classes=5, lr=1e-3 if adam else 0.05, seed=21, balance=[3, 3, 1])
+    run_pair(wl, 2 * wl.depth + 3, tol=CONV_TOL, adam=adam, negative=True)
+    Ws, bs = ps.init_weights(wl.layers, wl.seed)
+    x, _ = ps.make_inputs(wl, 6)
+    ref = orc.Oracle(wl.layers, Ws, bs, loss=wl.loss, lr=wl.lr, balance=wl.balance)
+    p = Pipeline(wl.layers, Ws, bs, loss=wl.loss, lr=wl.lr, balance=wl.balance)
+    ro = ref.infer(x)
+    out = p.infer(torch.from_numpy(x).cuda()).cpu().numpy()
+    assert max(rel(out[t], ro[t]) for t in range(wl.depth - 1, 6)) < CONV_TOL
+    assert rel(B.partime_get_buffer(p.ctx, 0, 1, 1, feat * h * 256), ref.get_buffer("act", 1, 1)[0]) < CONV_TOL
+    p.close()
+
+
 def test_bandwidth_probe_returns_a_plausible_rate():
     for mode in (0, 1, 2):
         g = B.partime_bandwidth_probe(64 << 20, mode, 5)
@@ -792,17 +807,25 @@ def test_skip_connections_fp32(balance, loss):
     gradient wait in delay lines as long as the stages they cross."""
     w = skip_workload([97, 131, 131, 131, 131, 131, 11], {2: 0, 4: 1, 3: 2}, ps.ACT_GELU, loss, lr=0.02, drift=0.05,
                       seed=41, balance=balance)
-    run_pair(w, 40)
+    run_pair(w, 40, min_move=1e-3)
     run_pair(w, 40, chunks=[(0, 1), (1, 2), (2, 3), (3, 21), (21, 40)], k=0)
+    if balance == [1, 3, 2] and loss == ps.LOSS_MSE:
+        assert_sees_updates(w, 16)
 
 
 def test_skip_connections_relu_bf16_adam_and_infer():
     w = skip_workload([200, 300, 300, 300, 260, 260, 7], {2: 0, 4: 3}, ps.ACT_RELU, ps.LOSS_CE, lr=0.02, drift=0.05,
                       seed=42, balance=[2, 2, 2])
-    run_pair(w, 30)
     run_pair(w, 30, bf16=True)
+    # at the fp32 bar the trajectory has to be unique: an undecided ReLU unit inside a stage changes the gradient that the
+    # target of a skip sends back through its delay line, which cannot be handed over through the C ABI
+    for l in w.layers[:-1]:
+        l.act = ps.ACT_GELU
+    run_pair(w, 30)
     w.lr = 1e-3
     run_pair(w, 30, adam=ADAM)
+    for l in w.layers[:-1]:
+        l.act = ps.ACT_RELU
     Ws, bs = ps.init_weights(w.layers, w.seed)
     x, _ = ps.make_inputs(w, 10)
     ref = orc.Oracle(w.layers, Ws, bs, loss=w.loss, lr=w.lr, balance=w.balance)
@@ -843,5 +866,5 @@ def test_inference_bf16_between_learning_calls():
 
 
 def test_skip_connections_wide_full_rows():
-    w = skip_workload([4096, 4096, 4096, 4096, 64], {2: 0}, ps.ACT_GELU, ps.LOSS_MSE, lr=1e-3, drift=0.01, seed=43)
-    run_pair(w, 10)
+    w = skip_workload([4096, 4096, 4096, 4096, 64], {2: 0}, ps.ACT_GELU, ps.LOSS_MSE, lr=0.02, drift=0.01, seed=43)
+    run_pair(w, 12, min_move=1e-3)

@@ -554,10 +554,11 @@ def test_kink_band_records_units_near_zero_and_takes_the_chosen_one_sided_deriva
     y = np.zeros((1, 1, 4), dtype=np.float32)                  # MSE: g = 2 (o - y) / 4 = o / 2
     y[0, 0, 3] = 1.0                                           # unit 3 has o = 0, so g = -0.5 (non-zero)
     y[0, 0, 1] = 0.0                                           # unit 1: o = 0, y = 0: g = 0, never recorded
+    # sizes of the units' terms, sum |w u| + |b|: 0.25, 1.5, 1 - 2^-20, 0.125 + 2^-20; the band is relative to them
     grads = {}
     for side in (0, 1, -1):
         ref = orc.Oracle(layers, [W], [b], loss=ps.LOSS_MSE, lr=0.0)
-        ref.set_kink_band(2.0 ** -10, side)
+        ref.set_kink_band(2.0 ** -16, side)                    # unit 3: 2^-20 < 2^-16 * 0.125 = 2^-19
         ref.step(x, y)
         cnt, ev = ref.take_kink_events()
         assert cnt == 2 and ev.tolist() == [[0, 0, 2], [0, 0, 3]]        # (tick, layer, unit); unit 0 and 1 are far / silent
@@ -567,6 +568,13 @@ def test_kink_band_records_units_near_zero_and_takes_the_chosen_one_sided_deriva
     assert grads[0].tolist() == [0.125, 0.0, g2, 0.0]                    # [z > 0]: unit 2 active, unit 3 not
     assert grads[1].tolist() == [0.125, 0.0, g2, g3]                     # band counted as active
     assert grads[-1].tolist() == [0.125, 0.0, 0.0, 0.0]                  # band counted as inactive
+    # the band is relative to the size of the unit's own terms: 2^-18 reaches unit 2 (terms of size 1: 2^-20 < 2^-18) but
+    # not unit 3 (terms of size 1/8: 2^-20 > 2^-21)
+    ref = orc.Oracle(layers, [W], [b], loss=ps.LOSS_MSE, lr=0.0)
+    ref.set_kink_band(2.0 ** -18, -1)
+    ref.step(x, y)
+    cnt, ev = ref.take_kink_events()
+    assert cnt == 1 and ev.tolist() == [[0, 0, 2]] and ref.get_grads(0)[1].tolist() == [0.125, 0.0, 0.0, 0.0]
     # a band that the units are outside of changes nothing and records nothing
     ref = orc.Oracle(layers, [W], [b], loss=ps.LOSS_MSE, lr=0.0)
     ref.set_kink_band(2.0 ** -21, 1)
