@@ -113,6 +113,23 @@ int partime_init(const partime_config *cfg, const float *const *w_host, const fl
 int partime_step(partime_ctx *ctx, const float *x_dev, const void *target_dev, int n_ticks, float *out_dev,
                  float *loss_dev);
 
+/*
+ * partime_step for callers that cannot allocate device memory: code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc.  Same arguments, same kernels and bit-identical results; the loss partials that
+ * partime_step keeps in a buffer of the context (one float per tile of the last stage and tick, summed in a fixed
+ * order by a small kernel at the end of each block of 1024 ticks) live in a static device array of the library
+ * instead (1 MiB + 4 KiB per GPU, held from the first partime_init on that GPU until the process ends), whose
+ * address is looked up once per device.  The call itself allocates and frees nothing, on the host or the device.
+ * Limits: dense pipelines of one stream run with one launch per tick (any `balance`, SGD or Adam, skip connections);
+ * at most 256 tiles in the last stage.  Anything else: PT_EUNSUPPORTED, nothing is enqueued.
+ * Every call on a GPU shares that GPU's array, whatever the context or stream: calls that overlap in time on one GPU
+ * race on it (the losses of the overlapping calls are then undefined; weights and outputs are not affected).  Nothing
+ * in it has to start at zero: every slot a call reads it has written before, so the leftovers of an earlier, larger
+ * call are never seen.
+ */
+int partime_step_noalloc(partime_ctx *ctx, const float *x_dev, const void *target_dev, int n_ticks, float *out_dev,
+                         float *loss_dev);
+
 /* n_ticks forward-only ticks (Eq. 6 only) on the same buffers; weights are left untouched. */
 int partime_infer(partime_ctx *ctx, const float *x_dev, int n_ticks, float *out_dev);
 

@@ -27,7 +27,7 @@ EXPORTS = [
     "partime_init", "partime_step", "partime_infer", "partime_get_state", "partime_set_state",
     "partime_get_buffer", "partime_set_buffer", "partime_get_tick", "partime_set_tick", "partime_set_lr",
     "partime_reset", "partime_sync", "partime_destroy", "partime_last_error", "partime_last_launch_count",
-    "partime_bandwidth_probe", "partime_get_opt_state", "partime_set_opt_state",
+    "partime_bandwidth_probe", "partime_get_opt_state", "partime_set_opt_state", "partime_step_noalloc",
 ]
 
 
@@ -68,6 +68,7 @@ def load():
     fp = ctypes.POINTER(ctypes.c_float)
     lib.partime_init.argtypes = [ctypes.POINTER(partime_config), fpp, fpp, ctypes.POINTER(vp)]
     lib.partime_step.argtypes = [vp, vp, vp, ctypes.c_int, vp, vp]
+    lib.partime_step_noalloc.argtypes = [vp, vp, vp, ctypes.c_int, vp, vp]
     lib.partime_infer.argtypes = [vp, vp, ctypes.c_int, vp]
     lib.partime_get_state.argtypes = [vp, ctypes.c_int, fp, fp]
     lib.partime_set_state.argtypes = [vp, ctypes.c_int, fp, fp]
@@ -130,6 +131,10 @@ def partime_init(layers, weights, biases, *, balance=None, n_streams=1, w_dtype=
 
 def partime_step(ctx, x_dev: int, target_dev: int, n_ticks: int, out_dev: int, loss_dev: int):
     _check(load().partime_step(ctx, x_dev, target_dev, n_ticks, out_dev, loss_dev))
+
+
+def partime_step_noalloc(ctx, x_dev: int, target_dev: int, n_ticks: int, out_dev: int, loss_dev: int):
+    _check(load().partime_step_noalloc(ctx, x_dev, target_dev, n_ticks, out_dev, loss_dev))
 
 
 def partime_infer(ctx, x_dev: int, n_ticks: int, out_dev: int):

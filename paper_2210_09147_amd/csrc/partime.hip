@@ -19,6 +19,7 @@
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <string>
 #include <vector>
@@ -833,6 +834,18 @@ __global__ __launch_bounds__(256) void probe_write_kernel(float4 *p, size_t n4, 
 // host side
 // ------------------------------------------------------------------------------------------------
 
+// Scratch of partime_step_noalloc: the per-tick loss partials of a block of ticks (one float per tile of the last
+// stage and tick) followed by one block of dummy loss slots.  It lives in the code object, so every device the
+// library runs on holds its own copy from the moment the module is loaded there until the process ends.  Host code
+// never uses the symbol as an address: scratch_for() asks the runtime where the array sits on a device.
+constexpr int kScratchParts = 256;                                        // most tiles the last stage may have
+constexpr size_t kScratchFloats = (size_t)kLossSlots * kScratchParts + kLossSlots;   // 1 MiB + 4 KiB
+static __device__ __align__(256) float g_scratch[kScratchFloats];
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mu;
+float *g_scratch_ptr[kMaxDevices] = {};
+
 thread_local std::string g_err;
 
 int fail(int code, const char *fmt, ...) {
@@ -850,6 +863,23 @@ int fail(int code, const char *fmt, ...) {
     hipError_t e_ = (expr);                                                                 \
     if (e_ != hipSuccess) return fail(PT_EHIP, "%s: %s", #expr, hipGetErrorString(e_));    \
   } while (0)
+
+// Address of g_scratch on `device` (which must be the current device): looked up once per device and kept.
+int scratch_for(int device, float **out) {
+  if (device < 0 || device >= kMaxDevices) return fail(PT_EUNSUPPORTED, "device %d: at most %d devices", device, kMaxDevices);
+  std::lock_guard<std::mutex> lk(g_scratch_mu);
+  if (!g_scratch_ptr[device]) {
+    int cur = -1;
+    HIP_TRY(hipGetDevice(&cur));
+    if (cur != device) return fail(PT_EINVAL, "scratch lookup for device %d while device %d is current", device, cur);
+    void *p = nullptr;
+    HIP_TRY(hipGetSymbolAddress(&p, HIP_SYMBOL(g_scratch)));
+    if (!p) return fail(PT_EHIP, "hipGetSymbolAddress gave a null address for the scratch array");
+    g_scratch_ptr[device] = static_cast<float *>(p);
+  }
+  *out = g_scratch_ptr[device];
+  return PT_OK;
+}
 
 unsigned short host_bf16_rne(float f) {
   uint32_t u;
@@ -1818,6 +1848,10 @@ int partime_init(const partime_config *cfg, const float *const *w_host, const fl
   } while (0)
 
   INIT_TRY(hipGetDevice(&c->device));
+  {
+    float *scr = nullptr;   // the static scratch of partime_step_noalloc, looked up once per device while it is current
+    if (int rcs = scratch_for(c->device, &scr)) return bail(rcs);
+  }
   hipDeviceProp_t prop;
   INIT_TRY(hipGetDeviceProperties(&prop, c->device));
   c->n_cu = prop.multiProcessorCount;
@@ -2060,9 +2094,13 @@ void partime_destroy(partime_ctx *ctx) {
   free_ctx(ctx);
 }
 
+// lossp / dummy: where the dense single-stream path keeps the loss partials of a block of ticks and the loss slots
+// nobody asked for (the context's own buffers, or the static scratch array)
 static int run_ticks(partime_ctx *c, const float *x_dev, const void *target_dev, int n_ticks, float *out_dev,
-                     float *loss_dev, bool learn) {
+                     float *loss_dev, bool learn, float *lossp = nullptr, float *dummy = nullptr) {
   const int pl = c->stages.empty() ? 1 : c->stages.back().n_parts;   // (the conv path keeps no dense stages)
+  if (!lossp) lossp = c->d_lossp;
+  if (!dummy) dummy = c->d_dummy;
   const dim3 grid((unsigned)c->tiles.size()), block(c->nw * 64);
   const unsigned char *tgt = static_cast<const unsigned char *>(target_dev);
   c->last_launches = 0;
@@ -2208,9 +2246,9 @@ static int run_ticks(partime_ctx *c, const float *x_dev, const void *target_dev,
       pa.tgt = tgt ? tgt + (size_t)base * c->tgt_bytes : nullptr;
       // ticks [base, base+k) of the call are scored against targets that precede the block
       pa.hist = base == 0 ? c->d_hist[c->hist_cur] : (tgt ? tgt + (size_t)(base - c->k) * c->tgt_bytes : nullptr);
-      pa.lossp = c->d_lossp;
+      pa.lossp = lossp;
       pa.loss = loss_dev ? loss_dev + base : nullptr;
-      pa.dummy = c->d_dummy;
+      pa.dummy = dummy;
       pa.bar = c->d_bar;
       pa.err = c->d_err;
       pa.bar_base = c->bar_count;
@@ -2246,8 +2284,8 @@ static int run_ticks(partime_ctx *c, const float *x_dev, const void *target_dev,
       if (learn && c->cfg.loss != PT_LOSS_NONE)
         a.tgt = i >= c->k ? tgt + (size_t)(i - c->k) * c->tgt_bytes
                           : c->d_hist[c->hist_cur] + (size_t)i * c->tgt_bytes;
-      a.lossp = c->d_lossp + (size_t)j * pl;
-      a.loss1 = loss_dev ? loss_dev + i : c->d_dummy;
+      a.lossp = lossp + (size_t)j * pl;
+      a.loss1 = loss_dev ? loss_dev + i : dummy;
       a.adam_c1 = a.adam_c2 = 0.f;
       if (c->cfg.optimizer == PT_OPT_ADAM) {
         // every tick is one optimiser step of every stage, counted from the first tick after init or reset
@@ -2282,7 +2320,7 @@ static int run_ticks(partime_ctx *c, const float *x_dev, const void *target_dev,
       }
     }
     if (learn && c->cfg.loss == PT_LOSS_MSE && loss_dev) {
-      hipLaunchKernelGGL(loss_finalize_kernel, dim3((n + 255) / 256), dim3(256), 0, c->stream, c->d_lossp, pl, n,
+      hipLaunchKernelGGL(loss_finalize_kernel, dim3((n + 255) / 256), dim3(256), 0, c->stream, lossp, pl, n,
                          loss_dev + base);
       ++c->last_launches;
     }
@@ -2325,6 +2363,23 @@ int partime_infer(partime_ctx *ctx, const float *x_dev, int n_ticks, float *out_
   if (n_ticks == 0) return PT_OK;
   if (!x_dev || !out_dev) return fail(PT_EINVAL, "partime_infer: null x_dev / out_dev");
   return run_ticks(ctx, x_dev, nullptr, n_ticks, out_dev, nullptr, false);
+}
+
+int partime_step_noalloc(partime_ctx *ctx, const float *x_dev, const void *target_dev, int n_ticks, float *out_dev,
+                         float *loss_dev) {
+  if (!ctx) return fail(PT_EINVAL, "partime_step_noalloc: null context");
+  if (n_ticks < 0) return fail(PT_EINVAL, "partime_step_noalloc: n_ticks < 0");
+  if (n_ticks == 0) return PT_OK;
+  if (!x_dev || !out_dev) return fail(PT_EINVAL, "partime_step_noalloc: null x_dev / out_dev");
+  if (!target_dev && ctx->cfg.loss != PT_LOSS_NONE) return fail(PT_EINVAL, "partime_step_noalloc: null target_dev");
+  if (ctx->cv || ctx->rb || ctx->ms || ctx->persistent)
+    return fail(PT_EUNSUPPORTED, "partime_step_noalloc: built for dense pipelines of one stream, one launch per tick");
+  const int pl = ctx->stages.back().n_parts;
+  if (pl > kScratchParts)
+    return fail(PT_EUNSUPPORTED, "partime_step_noalloc: the last stage has %d tiles, the static scratch holds %d", pl, kScratchParts);
+  float *scr = nullptr;
+  if (int rc = scratch_for(ctx->device, &scr)) return rc;
+  return run_ticks(ctx, x_dev, target_dev, n_ticks, out_dev, loss_dev, true, scr, scr + (size_t)kLossSlots * kScratchParts);
 }
 
 // wait for the stream and report an error a kernel raised on the device (a grid barrier that ran out)
