@@ -846,15 +846,16 @@ constexpr int kMaxDevices = 64;
 std::mutex g_scratch_mu;
 float *g_scratch_ptr[kMaxDevices] = {};
 
-thread_local std::string g_err;
+// Description of the last failure on this thread.  A plain array on purpose: a thread-local object with a destructor
+// is torn down while the process exits, in an order against the runtime's own exit handlers that the library does
+// not control.
+thread_local char g_err[512] = "";
 
 int fail(int code, const char *fmt, ...) {
-  char buf[512];
   va_list ap;
   va_start(ap, fmt);
-  vsnprintf(buf, sizeof buf, fmt, ap);
+  vsnprintf(g_err, sizeof g_err, fmt, ap);
   va_end(ap);
-  g_err = buf;
   return code;
 }
 
@@ -1092,7 +1093,6 @@ const void *pick_kernel(int nw, int nbuf, bool persistent, bool adam = false) {
     return persistent ? reinterpret_cast<const void *>(&persistent_kernel<WT, LEARN, NW_, NB_>)           \
                       : reinterpret_cast<const void *>(&tick_kernel<WT, LEARN, NW_, NB_>);
   PT_VARIANT(8, 1)
-  PT_VARIANT(4, 2)
 #undef PT_VARIANT
   return nullptr;
 }
@@ -1313,13 +1313,6 @@ int init_multistream(partime_ctx *c, const float *const *w_host, const float *co
   if ((rc = alloc_zero(&c->d_err, 1)) != PT_OK) return rc;
   c->msnet.err = c->d_err;
   MS_TRY(hipDeviceSynchronize());
-  if (std::getenv("PARTIME_DEBUG")) {
-    int nf = 0, nb = 0;
-    (void)hipOccupancyMaxActiveBlocksPerMultiprocessor(&nf, reinterpret_cast<const void *>(&ms_forward_kernel<true>), 256, 0);
-    (void)hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, reinterpret_cast<const void *>(&ms_backward_kernel<0>), 256, 0);
-    std::fprintf(stderr, "partime: multi-stream tiles f/b = %d/%d, resident work-groups per CU f/b = %d/%d\n",
-                 c->n_tiles_f, c->n_tiles_b, nf, nb);
-  }
   return PT_OK;
 }
 
@@ -1510,13 +1503,6 @@ int init_batched(partime_ctx *c, const float *const *w_host, const float *const 
   for (const void *k : {c->rb_k_fwd[0], c->rb_k_fwd[1], c->rb_k_bwd})
     MS_TRY(hipFuncSetAttribute(k, hipFuncAttributeMaxDynamicSharedMemorySize, (int)c->rb_lds_s));
   MS_TRY(hipFuncSetAttribute(c->rb_k_upd, hipFuncAttributeMaxDynamicSharedMemorySize, (int)c->rb_lds_u));
-  if (std::getenv("PARTIME_DEBUG")) {
-    int nf = 0, nu = 0;
-    (void)hipOccupancyMaxActiveBlocksPerMultiprocessor(&nf, c->rb_k_fwd[1], 2 * c->rb_tm, c->rb_lds_s);
-    (void)hipOccupancyMaxActiveBlocksPerMultiprocessor(&nu, c->rb_k_upd, 2 * c->rb_tm, c->rb_lds_u);
-    std::fprintf(stderr, "partime: batched tiles f/b/u = %d/%d/%d (first position), LDS %zu/%zu bytes, resident work-groups per CU f/u = %d/%d\n",
-                 c->rb_f_cnt[0], c->rb_b_cnt[0], c->rb_nu, c->rb_lds_s, c->rb_lds_u, nf, nu);
-  }
   if ((rc = alloc_zero(&c->d_dummy, (size_t)std::max(kLossSlots, c->out_dim))) != PT_OK) return rc;
   for (int p = 0; p < 2; ++p)
     if ((rc = alloc_zero(&c->d_hist[p], std::max<size_t>(1, (size_t)c->k) * c->tgt_bytes)) != PT_OK) return rc;
@@ -1754,7 +1740,7 @@ int init_conv(partime_ctx *c, const float *const *w_host, const float *const *b_
 
 extern "C" {
 
-const char *partime_last_error(void) { return g_err.c_str(); }
+const char *partime_last_error(void) { return g_err; }
 
 int partime_init(const partime_config *cfg, const float *const *w_host, const float *const *b_host,
                  partime_ctx **out) {
@@ -1857,27 +1843,26 @@ int partime_init(const partime_config *cfg, const float *const *w_host, const fl
   c->n_cu = prop.multiProcessorCount;
 
   c->tgt_bytes = c->cfg.loss == PT_LOSS_MSE ? (size_t)c->S * c->out_dim * 4 : (size_t)c->S * 4;
-  if (const char *e = std::getenv("PARTIME_SERPENTINE")) c->serpentine = std::atoi(e);
   if (const char *e = std::getenv("PARTIME_SPIN_LIMIT")) c->spin_limit = std::atoll(e);
   if (any_conv) {
     int rcc = init_conv(c, w_host, b_host, cfg->balance);
     if (rcc != PT_OK) return bail(rcc);
     *out = c;
-    g_err.clear();
+    g_err[0] = 0;
     return PT_OK;
   }
   if (c->S > kMsS) {
     int rcb = init_batched(c, w_host, b_host, cfg->balance);
     if (rcb != PT_OK) return bail(rcb);
     *out = c;
-    g_err.clear();
+    g_err[0] = 0;
     return PT_OK;
   }
   if (c->S > 1) {
     int rcm = init_multistream(c, w_host, b_host);
     if (rcm != PT_OK) return bail(rcm);
     *out = c;
-    g_err.clear();
+    g_err[0] = 0;
     return PT_OK;
   }
   // one record per layer ("node"); a stage is a run of nodes
@@ -1907,9 +1892,6 @@ int partime_init(const partime_config *cfg, const float *const *w_host, const fl
     s.rb = c->cfg.w_dtype == PT_F32 ? rows_per_iter<float>(s.nch) : rows_per_iter<bf16_t>(s.nch);
     if (c->cfg.w_dtype == PT_BF16 && s.nch > 8) return bail(fail(PT_EUNSUPPORTED, "partime_init: internal nch"));
   }
-  if (const char *e = std::getenv("PARTIME_VARIANT")) {
-    if (std::sscanf(e, "%dx%d", &c->nw, &c->nbuf) != 2) return bail(fail(PT_EINVAL, "PARTIME_VARIANT=%s", e));
-  }
   if (c->cfg.w_dtype == PT_F32) {
     c->k_learn = pick_kernel<float, true>(c->nw, c->nbuf, false);
     c->k_infer = pick_kernel<float, false>(c->nw, c->nbuf, false);
@@ -1928,7 +1910,6 @@ int partime_init(const partime_config *cfg, const float *const *w_host, const fl
     c->k_infer = c->cfg.w_dtype == PT_F32 ? pick_kernel<float, false>(8, 1, false) : pick_kernel<bf16_t, false>(8, 1, false);
   }
   if (!c->k_learn || !c->k_infer) return bail(fail(PT_EINVAL, "no kernel variant %dx%d", c->nw, c->nbuf));
-  if (const char *e = std::getenv("PARTIME_TILES_PER_CU")) c->tiles_per_cu = std::max(1, std::atoi(e));
   int rc = build_plan(c);
   if (rc != PT_OK) return bail(rc);
 
@@ -2077,14 +2058,13 @@ int partime_init(const partime_config *cfg, const float *const *w_host, const fl
   INIT_TRY(hipMalloc(&c->d_err, sizeof(int)));
   INIT_TRY(hipMemset(c->d_err, 0, sizeof(int)));
   c->persistent = c->cfg.exec_mode == PT_EXEC_PERSISTENT;
-  if (const char *e = std::getenv("PARTIME_EXEC")) c->persistent = std::atoi(e) == PT_EXEC_PERSISTENT;
   if (c->cmax > 1 || c->cfg.optimizer == PT_OPT_ADAM) c->persistent = false;   // no single-kernel form for these
   for (auto &l : c->layers)
     if (l.skip_from >= 0) c->persistent = false;
   INIT_TRY(hipDeviceSynchronize());
 #undef INIT_TRY
   *out = c;
-  g_err.clear();
+  g_err[0] = 0;
   return PT_OK;
 }
 

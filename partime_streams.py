@@ -173,21 +173,6 @@ def workload(cfg: int, ticks: Optional[int] = None) -> Workload:
         for dst in (2, 4, 6):
             w.layers[dst].skip_from = dst - 2
         w.name += "_skips"
-    elif cfg >= 300:
-        # size probes of the batched path: cfg = 300 + layer width / 128; 8 layers, replay batch of 1024, SGD
-        wd = (cfg - 300) * 128
-        w = Workload(f"mlp8x{wd}_bf16_b1024_mse_sgd", mlp([wd] * 9, ACT_RELU), n_streams=1024, w_dtype=W_BF16,
-                     loss=LOSS_MSE, lr=1e-5, ticks=100, drift=0.01, replay=True)
-    elif cfg >= 200:
-        # size probes of the multi-stream path: cfg = 200 + number of 4096 x 4096 bf16 layers, 32 streams
-        n = cfg - 200
-        w = Workload(f"mlp{n}x4096_bf16_s32_mse", mlp([4096] * (n + 1), ACT_RELU), n_streams=32, w_dtype=W_BF16,
-                     loss=LOSS_MSE, lr=1e-4, ticks=2000, drift=0.01)
-    elif cfg >= 100:
-        # size probes: cfg = 100 + number of 4096 x 4096 fp32 layers (64 MiB each)
-        n = cfg - 100
-        w = Workload(f"mlp{n}x4096_f32_relu_mse", mlp([4096] * (n + 1), ACT_RELU),
-                     loss=LOSS_MSE, lr=1e-4, ticks=2000, drift=0.005)
     else:
         raise ValueError(cfg)
     if ticks is not None:
