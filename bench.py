@@ -75,6 +75,17 @@ def read_traffic(name, mode):
     return float(m.group(1)) if m else None
 
 
+def read_mfma_util(name, mode):
+    """Matrix-pipe busy fraction of the kernels of one tick (SQ_VALU_MFMA_BUSY_CYCLES over SIMD-cycles of the launch)
+    from the committed rocprofv3 --pmc summary, if there is one."""
+    import glob
+    found = glob.glob(os.path.join(ROOT, "profiles", f"*_{name}_{mode}_mfma.txt"))
+    if not found:
+        return None
+    m = re.search(r"^mfma_util:\s*([0-9.eE+-]+)", open(found[0]).read(), flags=re.M)
+    return float(m.group(1)) if m else None
+
+
 def cpu_baseline(w, Ws, bs, budget_s=15.0):
     """The oracle as it stands, on the host cores, on the first ticks of the same stream (the generators are seeded, so
     these are the ticks the GPU run started with); the sample is drawn here, whatever --steps and --warmup are."""
@@ -208,7 +219,7 @@ def main():
     if w.n_streams >= 64:
         kernel_name = "rb_gemm_kernel (forward, backward, update) + rb_input / rb_head / rb_bias kernels (one tick)"
     elif w.n_streams > 1:
-        kernel_name = "ms_forward_kernel + ms_backward_kernel (one tick)"
+        kernel_name = "ms_vec_kernel + ms_mat_kernel (one tick)" if learn else "ms_infer_kernel"
     elif is_conv:
         kernel_name = "cv_conv_kernel (forward, backward-data) + cv_wgrad_kernel + cv_update_kernel (one tick)"
     else:
@@ -242,6 +253,8 @@ def main():
         if fl / 2.5e15 > abytes / (HBM_PEAK_GBS * 1e9):
             tf = rec["roofline"]["tflops"]
             rec["roofline"].update({"bound": "mfma", "achieved": tf, "peak": 2500.0, "unit": "TFLOP/s", "frac": tf / 2500.0})
+    if is_conv or w.n_streams > 1:
+        rec["roofline"]["mfma_util"] = read_mfma_util(w.name, args.mode)     # counted, not derived from flops / time
     p.close()
     del xd, td, out
     if not is_conv and not is_batched:

@@ -57,8 +57,9 @@ typedef struct {
   int c_in, c_out, h, w;
   int skip_from;       /* -1, or the index of an earlier layer whose output (same size) is added to this layer's
                           output after the activation (skip connections of Sec. V-C; the tensor and its gradient
-                          cross the stages in between one per tick, like the main path).  Dense layers, one stream or
-                          64 and more, not PT_EXEC_PERSISTENT; one skip per source layer; not into the last layer. */
+                          cross the stages in between one per tick, like the main path).  Dense layers of one stream
+                          or of 64 and more, and conv layers (equal channel counts); not PT_EXEC_PERSISTENT; one skip
+                          per source layer; not into the last layer. */
 } pt_layer;
 
 typedef struct {

@@ -51,6 +51,15 @@ struct CvStage {
   float *pred_delta;       // not the first of its stage: the layer in front of it (its z, then its delta) ...
   float *pred_dbp;         // ... and that layer's bias-gradient partials; NULL: publish the input-error (eout)
   int pred_act;
+  // Residual connections (Sec. V-C): the target layer adds the source's output of d ticks ago (d = stage boundaries
+  // crossed) after its own activation, and hands the gradient at its output back to the source over the same delay.
+  // Both travel through rings of d + 1 frames [co_pad][H][W], slot = tick mod (d + 1); the rings belong to the target.
+  const float *skip_in;    // this layer is a target: ring of the skipped map ...
+  float *serr_out;         // ... and ring its output-gradient is written to
+  int skip_n, skip_d;      // slots, delay
+  float *skip_out;         // this layer is a source: ring its output is also written to ...
+  const float *serr_in;    // ... and ring the gradient comes back over
+  int src_n, src_d;
 };
 
 struct CvHead {
@@ -82,6 +91,7 @@ struct CvTick {
   float *out;
   float *loss1;
   int cur, learn;
+  int tick;                 // tick number modulo a common multiple of all ring lengths (slots of the residual rings)
   float adam_c1, adam_c2;   // lr / (1 - beta1^n), 1 / sqrt(1 - beta2^n)
 };
 
@@ -193,6 +203,25 @@ __global__ __launch_bounds__(256, 2) void cv_conv_kernel(CvNet net, CvTick a) {
   const float *bias = sp->b;
   const int fuse_delta = sp->fuse_delta, pred_act = sp->pred_act;
   float *pred_delta = sp->pred_delta, *pred_dbp = sp->pred_dbp;
+  // residual rings, at the slots of this tick: the layer whose output (FWD) or output-gradient (FWD with the delta in
+  // its epilogue; BWD: the layer in front, whose delta this launch forms) is in hand
+  const float *skip_in = nullptr, *serr_in = nullptr;
+  float *skip_out = nullptr, *serr_out = nullptr;
+  {
+    const CvStage *rp = MODE == CV_FWD ? sp : sp - 1;
+    if (MODE == CV_FWD || pred_delta) {
+      const size_t frame = (size_t)rp->co_pad * H * sp->W;
+      const int t = a.tick;
+      if (rp->skip_in) {
+        if (MODE == CV_FWD) skip_in = rp->skip_in + (size_t)((t + rp->skip_n - rp->skip_d) % rp->skip_n) * frame;
+        if (LEARN) serr_out = rp->serr_out + (size_t)(t % rp->skip_n) * frame;
+      }
+      if (rp->skip_out) {
+        if (MODE == CV_FWD) skip_out = rp->skip_out + (size_t)(t % rp->src_n) * frame;
+        if (LEARN) serr_in = rp->serr_in + (size_t)((t + rp->src_n - rp->src_d) % rp->src_n) * frame;
+      }
+    }
+  }
   // FWD: input channels are the stage's inputs; BWD: the "input" is delta (64 channels), the output has c_in channels
   const float *src = MODE == CV_FWD ? (in_prev ? in_prev : a.x) : delta;
   // tap-major weights of this tile's block of 64 output channels: [k][64], k = (input channel) * 9 + tap
@@ -318,13 +347,37 @@ __global__ __launch_bounds__(256, 2) void cv_conv_kernel(CvNet net, CvTick a) {
             const int cc = FULL ? co : min(co, n_out - 1);       // padding channels: clamped load, never stored
             gv[r] = gin ? ldg_f(gin + (size_t)cc * HW + p) : ldg_f(ge + cc);
           }
+          if (serr_in) {      // the gradient that comes back over a residual connection starting at this output
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+              const int co = ch0 + cb * 32 + (r >> 2) * 8 + half * 4 + (r & 3);
+              gv[r] += ldg_f(serr_in + (size_t)(FULL ? co : min(co, n_out - 1)) * HW + p);
+            }
+          }
+          if (serr_out) {     // o = phi(z) + skipped map: the gradient at o goes to the skipped map unchanged
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+              const int co = ch0 + cb * 32 + (r >> 2) * 8 + half * 4 + (r & 3);
+              if (FULL || co < n_out) stg_f(serr_out + (size_t)co * HW + p, gv[r]);
+            }
+          }
+        }
+        float sk[16];
+        if (skip_in) {
+#pragma unroll
+          for (int r = 0; r < 16; ++r) {
+            const int co = ch0 + cb * 32 + (r >> 2) * 8 + half * 4 + (r & 3);
+            sk[r] = ldg_f(skip_in + (size_t)(FULL ? co : min(co, n_out - 1)) * HW + p);
+          }
         }
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
           const int co = ch0 + cb * 32 + (r >> 2) * 8 + half * 4 + (r & 3);
           if (!FULL && co >= n_out) continue;                    // padding channels are zero everywhere and stay so
           const float z = acc[q][r] + bz[r];
-          stg_f(outp + (size_t)co * HW + p, act_fwd(act, z));
+          const float o = skip_in ? act_fwd(act, z) + sk[r] : act_fwd(act, z);
+          stg_f(outp + (size_t)co * HW + p, o);
+          if (skip_out) stg_f(skip_out + (size_t)co * HW + p, o);
           if (LEARN) {
             if (fuse_delta) {
               const float d = gv[r] * act_der(act, z);
@@ -348,7 +401,10 @@ __global__ __launch_bounds__(256, 2) void cv_conv_kernel(CvNet net, CvTick a) {
         for (int r = 0; r < 16; ++r) {
           const int co = ch0 + cb * 32 + (r >> 2) * 8 + half * 4 + (r & 3);
           if (!FULL && co >= n_out) continue;
-          const float d = acc[q][r] * act_der(pred_act, zv[r]);
+          float gq = acc[q][r];                                  // gradient at the output of the layer in front
+          if (serr_in) gq += ldg_f(serr_in + (size_t)co * HW + p);
+          if (serr_out) stg_f(serr_out + (size_t)co * HW + p, gq);
+          const float d = gq * act_der(pred_act, zv[r]);
           stg_f(pred_delta + (size_t)co * HW + p, d);
           dsum[r] += d;
         }

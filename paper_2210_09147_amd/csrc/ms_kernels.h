@@ -1,15 +1,28 @@
-// Multi-stream (S > 1) stages: every stage product is a dense contraction with the S streams as its
+// Multi-stream (S = 32) stages: every stage product is a dense contraction with the S streams as its
 // narrow dimension, computed on the matrix cores (v_mfma_f32_16x16x32_bf16, gfx950) from bf16 weights.
 // Included by partime.hip only.
 //
-// One tick = two launches over all stages:
-//   ms_forward_kernel   Z = W rnd(X) + b, O = phi(Z) (Eq. 6; reads W once); in its epilogue g = the next
-//                       stage's error of the previous tick (Eq. 11), delta = rnd(g * phi'(Z)) in two layouts,
-//                       bias update
-//   ms_backward_kernel  E = W^T delta with the old W, W <- rnd(W - eta/S * delta X^T)   (Eq. 9, Eq. 11;
-//                       reads and writes W once).  Its first work-group runs the loss head of the last stage
-//                       (softmax / squared error over all outputs, delta, bias); the tiles of the last stage,
-//                       which come last in the launch, start once that work-group has raised its flag.
+// The weights are the traffic (arithmetic intensity 48 flop per byte), so a learning tick reads every weight once and
+// writes it once.  A stage's delta needs the stage's complete pre-activations, which would force a second pass; the
+// pass is therefore folded across the tick boundary: the launch that updates the weights of tick t also forms, from
+// the updated tile it still holds in registers, the tile's share of the NEXT tick's pre-activations.
+//
+// One learning tick = two launches over all stages:
+//   ms_vec_kernel   (vectors only)  z(t) = b + sum of the partial planes the previous matrix launch left (Eq. 6),
+//                   o = phi(z), published in fp32 and as bf16 in both orientations; g = the error the next stage
+//                   published one tick earlier (sum of its planes, Eq. 11), delta = rnd(g * phi'(z)) (Eq. 9) in both
+//                   orientations, bias update; rnd(x(t)) transposed and rnd(x(t+1)) for the first stage
+//   ms_mat_kernel   tile = up to 512 rows x 512 columns of one stage's W, one pass: E = W^T delta with the old W
+//                   (error plane of this row tile), W <- rnd(W - eta/S * delta rnd(x)^T)  (Algorithm 1, last two
+//                   steps), then Z(t+1) partial = W_new * rnd(x(t+1)) over the tile's columns (plane of this column
+//                   tile).  Its first work-group runs the loss head of the last stage (softmax / squared error over all
+//                   outputs, delta, bias); the tiles of the last stage, which come last in the launch, start once that
+//                   work-group has raised its flag.
+// x(t+1) of a stage is what the stage in front of it has just published, and for the first stage the caller's next
+// sample; at the last tick of a call that sample is not known yet, so the first stage's planes are formed by a
+// forward-only launch of the same kernel over that stage when the next call begins.  The same forward-only mode
+// forms every stage's planes for the first learning tick after inference ticks or after the state was changed from
+// outside.  An inference tick writes no weights, so nothing is gained by folding: it is one launch of ms_infer_kernel.
 // rnd() is round-to-nearest-even to bf16: what enters a matrix-core product is bf16, sums are fp32.
 //
 // Matrix-core operand layout used throughout (16x16x32, D = A * B + C, wave of 64 lanes, lane l, g = l / 16):
@@ -27,39 +40,33 @@ typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
 typedef float f32x4_t __attribute__((ext_vector_type(4)));
 
 constexpr int kMsS = 32;          // streams (fixed by the kernels' register layouts)
-#ifndef PT_MS_RW
-#define PT_MS_RW 16               // rows per wave in the forward kernel (16 or 32)
-#endif
-#ifndef PT_MS_BPF
-#define PT_MS_BPF 1              // backward kernel: double-buffer the weight blocks (0.7 % with one long tile per compute unit)
-#endif
-constexpr int kMsRW = PT_MS_RW;
-constexpr int kMsRowsF = 4 * kMsRW;   // rows per forward tile (4 waves)
-constexpr int kMsKC = 512;            // columns of X staged in LDS at a time
+constexpr int kMsTR = 512;        // rows per matrix tile
+constexpr int kMsNWM = 4;         // waves of a matrix work-group: one per SIMD
+constexpr int kMsSB = 4;          // groups of 32 columns a wave takes: 128 columns, its share of E is 64 registers
+constexpr int kMsTC = 32 * kMsSB * kMsNWM;   // columns per matrix tile (stage sizes are padded to whole column tiles)
+constexpr int kMsVR = 64;         // rows per tile of the vector kernel
+constexpr int kMsRW = 16;         // inference kernel: rows per wave
+constexpr int kMsRowsF = 4 * kMsRW;   // rows per inference tile (4 waves)
+constexpr int kMsKC = 512;        // columns of X staged in LDS at a time by the inference kernel
 constexpr int kMsXPitch = kMsKC + 8;
-#ifndef PT_MS_RT
-#define PT_MS_RT 4096
-#endif
-constexpr int kMsRT = PT_MS_RT;   // rows per backward tile.  Long tiles win: with 4096 a launch of the 8 x 4096 network is
-                                  // 257 tiles (one per compute unit, all resident) and runs 12 % faster than with 1024
-                                  // (929 tiles in two uneven rounds, four error planes per stage instead of one)
-constexpr int kMsCT = 128;        // columns per backward tile (stage sizes are padded to multiples of 512)
 
 struct MsStage {
   bf16_t *W;                 // [out_pad][in_pad]
   float *b;                  // [out_pad]
   float *mW, *vW, *mb, *vb;  // Adam moments, fp32, shaped like W and b (NULL under plain SGD)
-  int in_dim, out_dim, in_pad, out_pad, act, is_last;
-  const float *in_act[2];    // [S][in_pad] of the previous stage (NULL: first stage, input comes from the caller)
+  int in_dim, out_dim, in_pad, out_pad, act, is_last, is_first;
   float *out_act[2];         // [S][out_pad] (NULL: last stage, output goes to the caller)
-  float *zbuf;               // [S][out_pad] pre-activations of this tick
+  float *zp;                 // [n_ct][S][out_pad] partial pre-activations of the coming tick, one plane per column tile
+  int n_ct;
+  float *zbuf;               // last stage: [S][out_pad] pre-activations of this tick (the loss head reads them)
   bf16_t *dlt;               // [S][out_pad] delta
   bf16_t *dltT;              // [out_pad][S]
-  const bf16_t *xq_in[2];    // rnd(stage input) [S][in_pad], written by the previous stage's forward (NULL: first stage)
+  const bf16_t *xq_in[2];    // rnd(stage input) [S][in_pad], published by the previous stage (NULL: first stage)
   bf16_t *xq_out[2];         // rnd(stage output) [S][out_pad] for the next stage (NULL: last stage)
   const bf16_t *xT_in[2];    // rnd(stage input) transposed [in_pad][S]
   bf16_t *xT_out[2];         // rnd(stage output) transposed [out_pad][S] (NULL: last stage)
-  bf16_t *xT0;               // first stage only: rnd(x(t)) transposed, built by the delta kernel
+  bf16_t *xT0;               // first stage only: rnd(x(t)) transposed [in_pad][S]
+  bf16_t *xq0;               // first stage only: rnd(x of the coming tick) [S][in_pad]
   const float *gin[2];       // error planes of the next stage [n_gparts][S][out_pad]
   int n_gparts;
   float *eout[2];            // this stage's error planes [n_rt][S][in_pad] (NULL for the first stage)
@@ -73,35 +80,36 @@ struct MsView {
   bf16_t *W;
   float *b;
   float *mW, *vW, *mb, *vb;
-  int in_dim, out_dim, in_pad, out_pad, act, is_last;
-  const float *in_prev;
+  int in_dim, out_dim, in_pad, out_pad, act, is_last, is_first;
   float *out_cur;
+  float *zp;
+  int n_ct;
   float *zbuf;
   bf16_t *dlt, *dltT;
-  const bf16_t *xq_prev;
+  const bf16_t *xq_fwd;      // operand of the forward product (the half the launch was told to use; first stage: xq0)
   bf16_t *xq_cur;
-  const bf16_t *xT_prev;
+  const bf16_t *xT_prev;     // operand of the update product (first stage: xT0)
   bf16_t *xT_cur;
-  bf16_t *xT0;
+  bf16_t *xT0, *xq0;
   const float *gin_prev;
   int n_gparts;
   float *eout_cur;
   int n_rt;
 };
-__device__ __forceinline__ MsView ms_view(const MsStage *sp, int cur) {
+__device__ __forceinline__ MsView ms_view(const MsStage *sp, int cur, int fhalf) {
   MsView v;
   v.W = sp->W; v.b = sp->b;
   v.mW = sp->mW; v.vW = sp->vW; v.mb = sp->mb; v.vb = sp->vb;
   v.in_dim = sp->in_dim; v.out_dim = sp->out_dim; v.in_pad = sp->in_pad; v.out_pad = sp->out_pad;
-  v.act = sp->act; v.is_last = sp->is_last;
-  v.in_prev = cur ? sp->in_act[0] : sp->in_act[1];
+  v.act = sp->act; v.is_last = sp->is_last; v.is_first = sp->is_first;
   v.out_cur = cur ? sp->out_act[1] : sp->out_act[0];
+  v.zp = sp->zp; v.n_ct = sp->n_ct;
   v.zbuf = sp->zbuf; v.dlt = sp->dlt; v.dltT = sp->dltT;
-  v.xq_prev = cur ? sp->xq_in[0] : sp->xq_in[1];
+  v.xT0 = sp->xT0; v.xq0 = sp->xq0;
+  v.xq_fwd = sp->is_first ? sp->xq0 : (fhalf ? sp->xq_in[1] : sp->xq_in[0]);
   v.xq_cur = cur ? sp->xq_out[1] : sp->xq_out[0];
-  v.xT_prev = cur ? sp->xT_in[0] : sp->xT_in[1];
+  v.xT_prev = sp->is_first ? sp->xT0 : (cur ? sp->xT_in[0] : sp->xT_in[1]);
   v.xT_cur = cur ? sp->xT_out[1] : sp->xT_out[0];
-  v.xT0 = sp->xT0;
   v.gin_prev = cur ? sp->gin[0] : sp->gin[1];
   v.n_gparts = sp->n_gparts;
   v.eout_cur = cur ? sp->eout[1] : sp->eout[0];
@@ -110,27 +118,30 @@ __device__ __forceinline__ MsView ms_view(const MsStage *sp, int cur) {
 }
 
 struct MsTile {
-  int stage, a, b, kind;     // forward: a = row0.  loss head: rows [a, a+b).  backward: a = row tile, b = column tile
+  int stage, a, b, kind;     // vector kernel: kind 0: rows [a, a + 64); kind 1: columns [a, a + 64) of the first stage's input.
+                             // matrix kernel: kind 0: a = row tile, b = column tile; kind 2: the loss head
 };
 
 struct MsNet {
   const MsStage *stages;
-  const MsTile *tiles_f, *tiles_b;
+  const MsTile *tiles_v, *tiles_m, *tiles_f;   // vector launch; matrix launch of a learning tick; forward-only matrix launch
+  const MsTile *tiles_i;                       // inference launch (tile: a = first of 64 rows)
   int loss, out_dim, adam;
   float lr_over_s, inv_s, beta1, beta2, eps;
   unsigned int *head_flag;  // sequence number of the last tick whose loss head is finished
   int *err;                 // raised when a bounded wait runs out
   long long spin_limit;
-  int sweep;                // 1: every forward tile walks the column blocks of W in the same order
 };
 
 struct MsTick {
-  const float *x;     // [S][in_dim]
-  const void *tgt;    // [S] int32 or [S][out_dim] fp32
-  float *out;         // [S][out_dim]
+  const float *x;       // [S][in_dim] this tick's samples
+  const float *x_next;  // the coming tick's samples, or NULL when the caller has not supplied them yet
+  const void *tgt;      // [S] int32 or [S][out_dim] fp32
+  float *out;           // [S][out_dim]
   float *loss1;
   int cur, learn;
-  unsigned int seq;   // tick + 1: what the loss head writes to head_flag when it is done
+  int fhalf;            // which half of the published activations the forward product of this launch reads
+  unsigned int seq;     // tick + 1: what the loss head writes to head_flag when it is done
   float adam_c1, adam_c2;   // lr / (1 - beta1^n), 1 / sqrt(1 - beta2^n)
 };
 
@@ -159,24 +170,138 @@ __device__ __forceinline__ float ms_step(const MsNet &net, const MsTick &a, floa
 }
 
 // ------------------------------------------------------------------------------------------------
-// forward: tile = 4 * kMsRW rows of one stage x all columns; wave w owns kMsRW rows.  The weights go from
-// HBM straight into operand registers; the bf16 stage input, shared by the four waves, is staged through
-// LDS one block of columns at a time.  (Reading the shared operand from L2 in every wave instead was
-// measured 2.7x slower: all waves of the chip then hammer the same few hundred KB.)
+// vector kernel: everything of a tick that is a vector per stream.  Tile = 64 rows of one stage x the 32 streams;
+// thread (stream s, group of 8 rows).  The transposed bf16 copies go through LDS so that every store is 16 bytes.
 // ------------------------------------------------------------------------------------------------
-template <int ACT>
-__device__ __forceinline__ void ms_delta_body(const MsNet &net, const MsTick &a, const MsTile &tl, const MsView &st,
-                                              float *smax, float *ssum, float *sloss, float *sred);
-
 template <bool LEARN>
-__global__ __launch_bounds__(256) void ms_forward_kernel(MsNet net, MsTick a) {
+__global__ __launch_bounds__(256) void ms_vec_kernel(MsNet net, MsTick a) {
+  __shared__ __attribute__((aligned(16))) unsigned short tr[2][kMsVR * kMsS];   // bf16 [row][stream]: outputs, deltas
+  const MsTile tl = net.tiles_v[blockIdx.x];
+  const MsView st = ms_view(net.stages + tl.stage, a.cur, a.cur);
+  const int tid = threadIdx.x, s = tid >> 3, rq = tid & 7;
+  const int trow = tid >> 2, tq = tid & 3;           // transposed phase: row of the tile, group of 8 streams
+
+  if (tl.kind == 1) {
+    // first stage: the caller's fp32 samples rounded on the way in; columns [k0, k0 + 64) of the padded input.
+    // rnd(x(t)) transposed feeds the update product, rnd(x(t+1)) the forward product of the coming tick.
+    const int k = tl.a + 8 * rq;
+    auto round8 = [&](const float *x, unsigned int (&p)[4]) {
+      float v[8];
+#pragma unroll
+      for (int j = 0; j < 8; ++j) v[j] = ldg_f(x + (size_t)s * st.in_dim + min(k + j, st.in_dim - 1));   // clamped, unconditional
+#pragma unroll
+      for (int j = 0; j < 8; ++j) v[j] = k + j < st.in_dim ? v[j] : 0.f;
+#pragma unroll
+      for (int j = 0; j < 4; ++j) p[j] = pack_bf16(v[2 * j], v[2 * j + 1]);
+    };
+    if (a.x_next) {
+      unsigned int p[4];
+      round8(a.x_next, p);
+      stg16(st.xq0 + (size_t)s * st.in_pad + k, make_uint4(p[0], p[1], p[2], p[3]));
+    }
+    if (LEARN) {
+      unsigned int p[4];
+      round8(a.x, p);
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        tr[0][(8 * rq + 2 * j) * kMsS + s] = (unsigned short)(p[j] & 0xffffu);
+        tr[0][(8 * rq + 2 * j + 1) * kMsS + s] = (unsigned short)(p[j] >> 16);
+      }
+      __syncthreads();
+      stg16(st.xT0 + (size_t)(tl.a + trow) * kMsS + 8 * tq, *reinterpret_cast<const uint4 *>(&tr[0][trow * kMsS + 8 * tq]));
+    }
+    return;
+  }
+
+  // a1 (second half of Eq. 6): z = b + the column tiles' shares of W x, summed in a fixed order.  Rows beyond out_dim
+  // are padding: their weights and biases are zero, so z = o = 0 there and the padded stores are unconditional.
+  const int r = tl.a + 8 * rq;
+  const float4 b0 = ldg_f4(st.b + r), b1 = ldg_f4(st.b + r + 4);
+  float z[8] = {b0.x, b0.y, b0.z, b0.w, b1.x, b1.y, b1.z, b1.w};
+  {
+    const size_t plane = (size_t)kMsS * st.out_pad;
+    const float *zp = st.zp + (size_t)s * st.out_pad + r;
+    for (int q = 0; q < st.n_ct; ++q) {
+      const float4 u0 = ldg_f4(zp + q * plane), u1 = ldg_f4(zp + q * plane + 4);
+      z[0] += u0.x; z[1] += u0.y; z[2] += u0.z; z[3] += u0.w; z[4] += u1.x; z[5] += u1.y; z[6] += u1.z; z[7] += u1.w;
+    }
+  }
+  float o[8];
+#pragma unroll
+  for (int j = 0; j < 8; ++j) o[j] = act_fwd(st.act, z[j]);
+  if (st.is_last) {
+#pragma unroll
+    for (int j = 0; j < 8; ++j)
+      if (r + j < st.out_dim) stg_f(a.out + (size_t)s * st.out_dim + r + j, o[j]);
+    if (LEARN) {   // the loss head (first work-group of the matrix launch) needs every pre-activation of the stage
+      stg_f4(st.zbuf + (size_t)s * st.out_pad + r, make_float4(z[0], z[1], z[2], z[3]));
+      stg_f4(st.zbuf + (size_t)s * st.out_pad + r + 4, make_float4(z[4], z[5], z[6], z[7]));
+    }
+    return;
+  }
+  stg_f4(st.out_cur + (size_t)s * st.out_pad + r, make_float4(o[0], o[1], o[2], o[3]));
+  stg_f4(st.out_cur + (size_t)s * st.out_pad + r + 4, make_float4(o[4], o[5], o[6], o[7]));
+  unsigned int po[4], pd[4] = {0u, 0u, 0u, 0u};
+#pragma unroll
+  for (int j = 0; j < 4; ++j) po[j] = pack_bf16(o[2 * j], o[2 * j + 1]);
+  stg16(st.xq_cur + (size_t)s * st.out_pad + r, make_uint4(po[0], po[1], po[2], po[3]));
+  if (LEARN) {
+    // a3, a4: g = the error the next stage published one tick earlier (sum of its row-tile planes, Eq. 11),
+    // delta = rnd(g * phi'(z)) with this tick's z (Eq. 9).  Padding rows have z = 0 and g = 0, hence delta = 0.
+    const size_t plane = (size_t)kMsS * st.out_pad;
+    const float *gp = st.gin_prev + (size_t)s * st.out_pad + r;
+    float g[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    for (int q = 0; q < st.n_gparts; ++q) {
+      const float4 u0 = ldg_f4(gp + q * plane), u1 = ldg_f4(gp + q * plane + 4);
+      g[0] += u0.x; g[1] += u0.y; g[2] += u0.z; g[3] += u0.w; g[4] += u1.x; g[5] += u1.y; g[6] += u1.z; g[7] += u1.w;
+    }
+#pragma unroll
+    for (int j = 0; j < 4; ++j) pd[j] = pack_bf16(g[2 * j] * act_der(st.act, z[2 * j]), g[2 * j + 1] * act_der(st.act, z[2 * j + 1]));
+    stg16(st.dlt + (size_t)s * st.out_pad + r, make_uint4(pd[0], pd[1], pd[2], pd[3]));
+  }
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    tr[0][(8 * rq + 2 * j) * kMsS + s] = (unsigned short)(po[j] & 0xffffu);
+    tr[0][(8 * rq + 2 * j + 1) * kMsS + s] = (unsigned short)(po[j] >> 16);
+    if (LEARN) {
+      tr[1][(8 * rq + 2 * j) * kMsS + s] = (unsigned short)(pd[j] & 0xffffu);
+      tr[1][(8 * rq + 2 * j + 1) * kMsS + s] = (unsigned short)(pd[j] >> 16);
+    }
+  }
+  __syncthreads();
+  const int row = tl.a + trow;
+  stg16(st.xT_cur + (size_t)row * kMsS + 8 * tq, *reinterpret_cast<const uint4 *>(&tr[0][trow * kMsS + 8 * tq]));
+  if (LEARN) {
+    const uint4 d = *reinterpret_cast<const uint4 *>(&tr[1][trow * kMsS + 8 * tq]);
+    stg16(st.dltT + (size_t)row * kMsS + 8 * tq, d);
+    // a6 for the bias: b <- b - eta / S * sum over the streams of the rounded delta (what every product sees)
+    float dsum = bf16_lo(d.x) + bf16_hi(d.x) + bf16_lo(d.y) + bf16_hi(d.y) + bf16_lo(d.z) + bf16_hi(d.z) + bf16_lo(d.w) + bf16_hi(d.w);
+    dsum += __shfl_xor(dsum, 1, 64);
+    dsum += __shfl_xor(dsum, 2, 64);
+    if (tq == 0) {
+      float mq = net.adam ? ldg_f(st.mb + row) : 0.f, vq = net.adam ? ldg_f(st.vb + row) : 0.f;
+      stg_f(st.b + row, ms_step(net, a, ldg_f(st.b + row), dsum, mq, vq));
+      if (net.adam) {
+        stg_f(st.mb + row, mq);
+        stg_f(st.vb + row, vq);
+      }
+    }
+  }
+}
+
+// ------------------------------------------------------------------------------------------------
+// inference tick (Eq. 6 only): one launch, nothing is folded across the tick boundary because nothing is written to
+// the weights.  Tile = 64 rows of one stage x all columns, wave w owns 16 rows; the weights go from HBM straight into
+// operand registers, the bf16 stage input, shared by the four waves, is staged through LDS one block of 512 columns at
+// a time.  (Reading the shared operand from L2 in every wave instead was measured 2.7x slower.)
+// ------------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void ms_infer_kernel(MsNet net, MsTick a) {
   constexpr int NB = kMsRW / 16;   // 16-row blocks per wave
   __shared__ __attribute__((aligned(16))) unsigned short xs[2][kMsS * kMsXPitch];
-  const MsTile tl = net.tiles_f[blockIdx.x];
-  const MsView st = ms_view(net.stages + tl.stage, a.cur);
+  const MsTile tl = net.tiles_i[blockIdx.x];
+  const MsView st = ms_view(net.stages + tl.stage, a.cur, a.cur ^ 1);
   const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6, li = lane & 15, g = lane >> 4;
-  const int prev = a.cur ^ 1;
-  const bf16_t *xq = st.xq_prev;
+  const bf16_t *xq = st.is_first ? nullptr : st.xq_fwd;   // what the stage in front published one tick earlier
   const int r0 = tl.a + kMsRW * wv;                    // out_pad is a multiple of the tile: always in range
   const bf16_t *wrow = st.W + (size_t)(r0 + li) * st.in_pad + g * 8;
   const size_t blk = (size_t)16 * st.in_pad;
@@ -189,7 +314,7 @@ __global__ __launch_bounds__(256) void ms_forward_kernel(MsNet net, MsTick a) {
   // All tiles of a launch are resident together.  Walking the column blocks in the same order everywhere (sweep)
   // was measured 13 % faster in forward-only ticks than starting every tile at a different block.
   const int n_chunks = (st.in_pad + kMsKC - 1) / kMsKC;
-  const int c_first = net.sweep ? 0 : (int)(blockIdx.x % (unsigned)n_chunks);
+  const int c_first = 0;
   auto chunk_at = [&](int ci) { return ((ci + c_first) % n_chunks) * kMsKC; };
 
   // X blocks are double buffered: block ci+1 is fetched into registers while block ci is multiplied, then
@@ -303,32 +428,16 @@ __global__ __launch_bounds__(256) void ms_forward_kernel(MsNet net, MsTick a) {
   float4 bias[NB];
 #pragma unroll
   for (int b = 0; b < NB; ++b) bias[b] = ldg_f4(st.b + r0 + 16 * b + 4 * g);
-  // the first plane of the error signal is requested together with the biases: one memory latency for both
-  const bool hidden = LEARN && !st.is_last;
-  float4 g0[NB][2];
-  if (hidden) {
-#pragma unroll
-    for (int b = 0; b < NB; ++b)
-#pragma unroll
-      for (int h = 0; h < 2; ++h)
-        g0[b][h] = ldg_f4(st.gin_prev + (size_t)(16 * h + li) * st.out_pad + r0 + 16 * b + 4 * g);
-  }
-  __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
   for (int b = 0; b < NB; ++b) {
     const int rb = r0 + 16 * b + 4 * g;
     const float bb[4] = {bias[b].x, bias[b].y, bias[b].z, bias[b].w};
-    float dsum[4] = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int h = 0; h < 2; ++h) {
       const int s = 16 * h + li;
-      float z[4], o[4];
+      float o[4];
 #pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        z[j] = acc[b][h][j] + bb[j];
-        o[j] = act_fwd(st.act, z[j]);
-      }
-      if (LEARN && st.is_last) stg_f4(st.zbuf + (size_t)s * st.out_pad + rb, make_float4(z[0], z[1], z[2], z[3]));   // for the loss head
+      for (int j = 0; j < 4; ++j) o[j] = act_fwd(st.act, acc[b][h][j] + bb[j]);
       if (st.is_last) {
 #pragma unroll
         for (int j = 0; j < 4; ++j)
@@ -344,69 +453,6 @@ __global__ __launch_bounds__(256) void ms_forward_kernel(MsNet net, MsTick a) {
         stg_u16(t + 2 * kMsS, p23 & 0xffffu);
         stg_u16(t + 3 * kMsS, p23 >> 16);
       }
-      if (hidden) {
-        // a3, a4: g = the error the next stage published one tick earlier (sum of its row-tile planes, Eq. 11),
-        // delta = rnd(g * phi'(z)) with this tick's z (Eq. 9), stored in both orientations for the two products
-        // of the backward launch.  Padding rows have z = 0 and g = 0, hence delta = 0.
-        const size_t plane = (size_t)kMsS * st.out_pad;
-        const float *gp = st.gin_prev + (size_t)s * st.out_pad + rb;
-        float4 gs = g0[b][h];
-        for (int q = 1; q < st.n_gparts; ++q) {
-          const float4 v = ldg_f4(gp + q * plane);
-          gs.x += v.x; gs.y += v.y; gs.z += v.z; gs.w += v.w;
-        }
-        const unsigned int d01 = pack_bf16(gs.x * act_der(st.act, z[0]), gs.y * act_der(st.act, z[1]));
-        const unsigned int d23 = pack_bf16(gs.z * act_der(st.act, z[2]), gs.w * act_der(st.act, z[3]));
-        stg8(st.dlt + (size_t)s * st.out_pad + rb, make_uint2(d01, d23));
-        bf16_t *t = st.dltT + (size_t)rb * kMsS + s;
-        stg_u16(t, d01 & 0xffffu);
-        stg_u16(t + kMsS, d01 >> 16);
-        stg_u16(t + 2 * kMsS, d23 & 0xffffu);
-        stg_u16(t + 3 * kMsS, d23 >> 16);
-        // the rounded delta is what the bias update sees, like every product
-        dsum[0] += bf16_lo(d01); dsum[1] += bf16_hi(d01); dsum[2] += bf16_lo(d23); dsum[3] += bf16_hi(d23);
-      }
-    }
-    if (hidden) {
-      // a6 for the bias: b <- b - eta / S * sum over the streams (the 16 lanes li and the two halves h)
-#pragma unroll
-      for (int j = 0; j < 4; ++j) {
-#pragma unroll
-        for (int m = 1; m < 16; m <<= 1) dsum[j] += __shfl_xor(dsum[j], m, 64);
-      }
-      if (li == 0) {
-        float mq[4] = {0.f, 0.f, 0.f, 0.f}, vq[4] = {0.f, 0.f, 0.f, 0.f}, bn[4];
-        if (net.adam) {
-          const float4 m4 = ldg_f4(st.mb + rb), v4 = ldg_f4(st.vb + rb);
-          mq[0] = m4.x; mq[1] = m4.y; mq[2] = m4.z; mq[3] = m4.w;
-          vq[0] = v4.x; vq[1] = v4.y; vq[2] = v4.z; vq[3] = v4.w;
-        }
-#pragma unroll
-        for (int j = 0; j < 4; ++j) bn[j] = ms_step(net, a, bb[j], dsum[j], mq[j], vq[j]);
-        stg_f4(st.b + rb, make_float4(bn[0], bn[1], bn[2], bn[3]));
-        if (net.adam) {
-          stg_f4(st.mb + rb, make_float4(mq[0], mq[1], mq[2], mq[3]));
-          stg_f4(st.vb + rb, make_float4(vq[0], vq[1], vq[2], vq[3]));
-        }
-      }
-    }
-  }
-  if (!LEARN) return;
-  if (!st.xq_prev) {
-    // first stage: rnd(x(t)) transposed for the update product (later stages get theirs from the previous stage's
-    // forward pass); the stage's tiles share the columns among themselves
-    const int n_t = st.out_pad / kMsRowsF, per = (st.in_pad + n_t - 1) / n_t, k0 = (tl.a / kMsRowsF) * per;
-    for (int k = k0 + tid; k < min(k0 + per, st.in_pad); k += 256) {
-      const int kc = min(k, st.in_dim - 1);
-      float v[kMsS];
-#pragma unroll
-      for (int s = 0; s < kMsS; ++s) v[s] = ldg_f(a.x + (size_t)s * st.in_dim + kc);
-      unsigned int p[kMsS / 2];
-#pragma unroll
-      for (int s = 0; s < kMsS; s += 2) p[s / 2] = k < st.in_dim ? pack_bf16(v[s], v[s + 1]) : 0u;
-      bf16_t *dst = st.xT0 + (size_t)k * kMsS;
-#pragma unroll
-      for (int q = 0; q < kMsS / 8; ++q) stg16(dst + 8 * q, make_uint4(p[4 * q], p[4 * q + 1], p[4 * q + 2], p[4 * q + 3]));
     }
   }
 }
@@ -417,7 +463,7 @@ __global__ __launch_bounds__(256) void ms_forward_kernel(MsNet net, MsTick a) {
 // ------------------------------------------------------------------------------------------------
 // The activation is a template parameter: with a run-time switch inside the element loops every load sits in its
 // own basic block and is waited for before the next one is issued.
-template <int ACT>
+template <int ACT, int NT>
 __device__ __forceinline__ void ms_delta_body(const MsNet &net, const MsTick &a, const MsTile &tl, const MsView &st,
                                               float *smax, float *ssum, float *sloss, float *sred) {
   const int tid = threadIdx.x;
@@ -425,7 +471,7 @@ __device__ __forceinline__ void ms_delta_body(const MsNet &net, const MsTick &a,
   const float inv_n = 1.f / (float)net.out_dim;
   if (ce) {
     // softmax statistics per stream over the whole stage (this tile covers it): 8 lanes share a stream
-    {
+    if (tid < 8 * kMsS) {
       const int s = tid >> 3, part = tid & 7;
       const float *z = st.zbuf + (size_t)s * st.out_pad;
       float m = -INFINITY;
@@ -459,7 +505,7 @@ __device__ __forceinline__ void ms_delta_body(const MsNet &net, const MsTick &a,
     }
   }
   float sq = 0.f;
-  for (int r = tl.a + tid; r < tl.a + tl.b; r += 256) {
+  for (int r = tl.a + tid; r < tl.a + tl.b; r += NT) {
     float dsum = 0.f;
     bf16_t *dstT = st.dltT + (size_t)r * kMsS;
     const bool valid = r < st.out_dim;
@@ -519,36 +565,248 @@ __device__ __forceinline__ void ms_delta_body(const MsNet &net, const MsTick &a,
     sq = wave_sum(sq);
     if ((tid & 63) == 0) sred[tid >> 6] = sq;
     __syncthreads();
-    if (tid == 0) a.loss1[0] = a.learn ? (sred[0] + sred[1] + sred[2] + sred[3]) * inv_n * net.inv_s : 0.f;
+    if (tid == 0) {
+      float t = 0.f;
+      for (int w = 0; w < NT / 64; ++w) t += sred[w];
+      a.loss1[0] = a.learn ? t * inv_n * net.inv_s : 0.f;
+    }
   }
 }
 
 // ------------------------------------------------------------------------------------------------
-// backward + update: tile = up to kMsRT rows x 128 columns of one stage; wave w takes the 32-row blocks
-// w, w + 4, ...; every wave keeps its own share of E = W^T delta for the tile's 128 columns (64 VGPRs)
+// matrix kernel: tile = up to kMsTR rows x kMsTC columns of one stage; the four waves share the rows and take 128
+// columns each, so a wave keeps its share of E = W^T delta for its own columns to itself (64 VGPRs), while the four
+// shares of the coming tick's Z for a block of 32 rows meet in LDS (one work-group barrier per block).
+// MODE 0: a learning tick (E, update, forward of the coming tick); MODE 1: forward only.
 // ------------------------------------------------------------------------------------------------
-template <int OPT>
-__global__ __launch_bounds__(256) void ms_backward_kernel(MsNet net, MsTick a) {
-  __shared__ __attribute__((aligned(16))) float red[2][64 * 64];
-  const MsTile tl = net.tiles_b[blockIdx.x];
-  const MsView st = ms_view(net.stages + tl.stage, a.cur);
+
+// what a wave holds of one block of 32 rows: its 32 x 128 weights and, for a learning tick, the deltas of those rows
+// in the two operand layouts.  Everything is requested one block ahead, the deltas together with the weights: the
+// memory counter of this chip retires in order, so a load that is issued after the prefetch and awaited before the
+// arithmetic would make the arithmetic wait for the prefetch as well.
+struct MsBlock {
+  uint4 w[kMsSB][2];   // W[r0 + 16 b + li][c0 + 32 sb + 8 g .. + 7]
+  uint4 de[2];     // delta as B operand of E (contraction over the 32 rows): rows r0 + 16 b + 4 g + j at stream 16 h + li
+  uint4 du[2];     // delta^T as B operand of the update (contraction over the 32 streams): row r0 + 16 b + li, streams 8 g ..
+};
+
+template <int MODE, int OPT, bool HAS_E, bool FWD>
+__device__ __forceinline__ void ms_mat_tile(const MsNet &net, const MsTick &a, const MsTile &tl, const MsView &st,
+                                            float (&zred)[2][kMsNWM][1024]) {
   const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6, li = lane & 15, g = lane >> 4;
-  if (tl.kind == 2) {
+  const int row_lo = tl.a * kMsTR, row_hi = min(row_lo + kMsTR, st.out_pad);   // multiples of 32 (sizes are padded)
+  const int c0 = tl.b * kMsTC + 32 * kMsSB * wv;                                      // this wave's 128 columns
+
+  // selectors that move a 16 x 32 register block into C layout (multiplication by a 0/1 matrix is exact)
+  uint4 isel[2];
+#pragma unroll
+  for (int c = 0; c < 2; ++c) {
+    unsigned int w[4] = {0u, 0u, 0u, 0u};
+    const int m = c * 16 + li - g * 8;                 // element of this lane's 8 that must be 1.0
+    if (m >= 0 && m < 8) w[m >> 1] = (m & 1) ? 0x3f800000u : 0x00003f80u;
+    isel[c] = make_uint4(w[0], w[1], w[2], w[3]);
+  }
+  // update operand A = rnd(X)[k(slot)][s]: slot = l % 16 = 4 q + jj  ->  k = c0 + 32 sb + 8 q + 4 e + jj
+  uint4 xop[kMsSB][2];
+  // forward operand B = rnd(X_next)[k][s]: lane (stream 16 h + li) holds k = c0 + 32 sb + 8 g .. + 7
+  uint4 xf[kMsSB][2];
+#pragma unroll
+  for (int sb = 0; sb < kMsSB; ++sb)
+#pragma unroll
+    for (int e = 0; e < 2; ++e) {
+      if (MODE == 0) {
+        const int k = c0 + 32 * sb + 8 * (li >> 2) + 4 * e + (li & 3);
+        xop[sb][e] = ldg16(st.xT_prev + (size_t)k * kMsS + g * 8);
+      }
+      if (FWD) xf[sb][e] = ldg16(st.xq_fwd + (size_t)(16 * e + li) * st.in_pad + c0 + 32 * sb + g * 8);
+    }
+  f32x4_t eacc[kMsSB][2][2];
+#pragma unroll
+  for (int sb = 0; sb < kMsSB; ++sb)
+#pragma unroll
+    for (int c = 0; c < 2; ++c)
+#pragma unroll
+      for (int h = 0; h < 2; ++h) eacc[sb][c][h] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+
+  const float scale = net.lr_over_s;
+  auto load_block = [&](MsBlock &k, int r0) {
+#pragma unroll
+    for (int sb = 0; sb < kMsSB; ++sb)
+#pragma unroll
+      for (int b = 0; b < 2; ++b)
+        k.w[sb][b] = ldg16(st.W + (size_t)(r0 + 16 * b + li) * st.in_pad + c0 + 32 * sb + g * 8);
+    if (MODE == 0) {
+#pragma unroll
+      for (int h = 0; h < 2; ++h) {
+        const bf16_t *dp = st.dlt + (size_t)(16 * h + li) * st.out_pad + r0 + 4 * g;
+        const uint2 lo = ldg8(dp), hi = ldg8(dp + 16);
+        k.de[h] = make_uint4(lo.x, lo.y, hi.x, hi.y);
+      }
+#pragma unroll
+      for (int b = 0; b < 2; ++b) k.du[b] = ldg16(st.dltT + (size_t)(r0 + 16 * b + li) * kMsS + g * 8);
+    }
+  };
+  auto process_block = [&](MsBlock &k, int r0, int slot) {
+    f32x4_t facc[2][2];
+#pragma unroll
+    for (int b = 0; b < 2; ++b)
+#pragma unroll
+      for (int h = 0; h < 2; ++h) facc[b][h] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+    if (MODE == 0) {
+      // Adam: the moments of 32 columns (both 16-row halves) travel one column group ahead of the arithmetic
+      float4 mv[OPT == 1 ? 2 : 1][2][4];
+      auto load_mv = [&](int buf, int sb) {
+#pragma unroll
+        for (int b = 0; b < 2; ++b) {
+          const size_t off = (size_t)(r0 + 16 * b + li) * st.in_pad + c0 + 32 * sb + g * 8;
+          mv[buf][b][0] = ldg_f4(st.mW + off); mv[buf][b][1] = ldg_f4(st.mW + off + 4);
+          mv[buf][b][2] = ldg_f4(st.vW + off); mv[buf][b][3] = ldg_f4(st.vW + off + 4);
+        }
+      };
+      if (OPT == 1) load_mv(0, 0);
+#pragma unroll
+      for (int sb = 0; sb < kMsSB; ++sb) {
+        if (OPT == 1 && sb + 1 < kMsSB) load_mv((sb + 1) & 1, sb + 1);
+        if (HAS_E) {
+          // a5: E[k][s] += sum_r W[r][k] delta[r][s] with the rows as loaded (not yet updated)
+#pragma unroll
+          for (int c = 0; c < 2; ++c) {
+            const f32x4_t z4 = {0.f, 0.f, 0.f, 0.f};
+            const f32x4_t t0 = mfma16(k.w[sb][0], isel[c], z4);   // W[r0 + 4 g + j][c0 + 32 sb + 16 c + li]
+            const f32x4_t t1 = mfma16(k.w[sb][1], isel[c], z4);   // rows + 16
+            const uint4 wt = make_uint4(pack_bf16(t0[0], t0[1]), pack_bf16(t0[2], t0[3]),
+                                        pack_bf16(t1[0], t1[1]), pack_bf16(t1[2], t1[3]));
+#pragma unroll
+            for (int h = 0; h < 2; ++h) eacc[sb][c][h] = mfma16(wt, k.de[h], eacc[sb][c][h]);
+          }
+        }
+        // a6: W <- rnd(W - eta/S * delta rnd(X)^T); the product comes out as lane (row li, k = 8 g + 4 e + j)
+#pragma unroll
+        for (int b = 0; b < 2; ++b) {
+          const f32x4_t z4 = {0.f, 0.f, 0.f, 0.f};
+          const uint4 w = k.w[sb][b];
+          const f32x4_t u0 = mfma16(xop[sb][0], k.du[b], z4);
+          const f32x4_t u1 = mfma16(xop[sb][1], k.du[b], z4);
+          const size_t off = (size_t)(r0 + 16 * b + li) * st.in_pad + c0 + 32 * sb + g * 8;
+          uint4 o;
+          if (OPT == 1) {
+            // Adam: the moments of the lane's 8 weights, fp32, in and out
+            const float4 m0 = mv[sb & 1][b][0], m1 = mv[sb & 1][b][1], v0 = mv[sb & 1][b][2], v1 = mv[sb & 1][b][3];
+            float wq[8] = {bf16_lo(w.x), bf16_hi(w.x), bf16_lo(w.y), bf16_hi(w.y), bf16_lo(w.z), bf16_hi(w.z), bf16_lo(w.w), bf16_hi(w.w)};
+            const float gq[8] = {u0[0], u0[1], u0[2], u0[3], u1[0], u1[1], u1[2], u1[3]};
+            float mq[8] = {m0.x, m0.y, m0.z, m0.w, m1.x, m1.y, m1.z, m1.w}, vq[8] = {v0.x, v0.y, v0.z, v0.w, v1.x, v1.y, v1.z, v1.w};
+#pragma unroll
+            for (int e = 0; e < 8; ++e) wq[e] = ms_step(net, a, wq[e], gq[e], mq[e], vq[e]);
+            stg_f4(st.mW + off, make_float4(mq[0], mq[1], mq[2], mq[3]));
+            stg_f4(st.mW + off + 4, make_float4(mq[4], mq[5], mq[6], mq[7]));
+            stg_f4(st.vW + off, make_float4(vq[0], vq[1], vq[2], vq[3]));
+            stg_f4(st.vW + off + 4, make_float4(vq[4], vq[5], vq[6], vq[7]));
+            o = make_uint4(pack_bf16(wq[0], wq[1]), pack_bf16(wq[2], wq[3]), pack_bf16(wq[4], wq[5]), pack_bf16(wq[6], wq[7]));
+          } else {
+            o.x = pack_bf16(bf16_lo(w.x) - scale * u0[0], bf16_hi(w.x) - scale * u0[1]);
+            o.y = pack_bf16(bf16_lo(w.y) - scale * u0[2], bf16_hi(w.y) - scale * u0[3]);
+            o.z = pack_bf16(bf16_lo(w.z) - scale * u1[0], bf16_hi(w.z) - scale * u1[1]);
+            o.w = pack_bf16(bf16_lo(w.w) - scale * u1[2], bf16_hi(w.w) - scale * u1[3]);
+          }
+          stg16(st.W + off, o);
+          // a1 of the coming tick (first half of Eq. 6) with the weights as just stored
+          if (FWD) {
+#pragma unroll
+            for (int h = 0; h < 2; ++h) facc[b][h] = mfma16(o, xf[sb][h], facc[b][h]);
+          }
+        }
+      }
+    } else {
+#pragma unroll
+      for (int sb = 0; sb < kMsSB; ++sb)
+#pragma unroll
+        for (int b = 0; b < 2; ++b)
+#pragma unroll
+          for (int h = 0; h < 2; ++h) facc[b][h] = mfma16(k.w[sb][b], xf[sb][h], facc[b][h]);
+    }
+    if (!FWD) return;
+    // the four waves' shares of Z for these 32 rows meet in LDS and are added in a fixed order.  Two slots: the
+    // barrier of block i + 1 stands between the reads of block i and the writes of block i + 2.
+#pragma unroll
+    for (int b = 0; b < 2; ++b)
+#pragma unroll
+      for (int h = 0; h < 2; ++h)
+        *reinterpret_cast<f32x4_t *>(&zred[slot][wv][(b * 2 + h) * 256 + lane * 4]) = facc[b][h];
+    // A plain work-group barrier also waits for every global access in flight, i.e. for this block's weight stores and
+    // for the next block's prefetch: only the LDS writes have to be complete here.
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+    if (kMsNWM == 4 || tid < 256) {
+      f32x4_t t = *reinterpret_cast<const f32x4_t *>(&zred[slot][0][tid * 4]);
+#pragma unroll
+      for (int w = 1; w < kMsNWM; ++w) t += *reinterpret_cast<const f32x4_t *>(&zred[slot][w][tid * 4]);
+      // position tid = (b, h, lane'): rows r0 + 16 b + 4 g' + j of stream 16 h + li'
+      const int b = tid >> 7, h = (tid >> 6) & 1, l2 = tid & 63;
+      float *dst = st.zp + ((size_t)tl.b * kMsS + 16 * h + (l2 & 15)) * st.out_pad + r0 + 16 * b + 4 * (l2 >> 4);
+      stg_f4(dst, make_float4(t[0], t[1], t[2], t[3]));
+    }
+  };
+  {
+    // Two register sets: the next block of 32 rows is requested before the current one is worked on.  The loop has no
+    // data-dependent branch (a tile is a whole number of 64-row pairs; the request after the last block is clamped
+    // onto the last block and never used): where paths with different numbers of requests in flight meet, the
+    // compiler has to wait for all of them, and the prefetch would no longer run ahead of the arithmetic.
+    MsBlock ka, kb;
+    // Odd ticks walk the tile's rows from the bottom up: what a tick wrote last is what the next tick reads first, while
+    // it is still in the memory-side cache.
+    const int n_blk = (row_hi - row_lo) >> 5;
+    const bool rev = (a.cur & 1) != 0;
+    auto row_of = [&](int i) { return rev ? row_hi - 32 - 32 * i : row_lo + 32 * i; };
+    load_block(ka, row_of(0));
+    for (int i = 0; i < n_blk; i += 2) {
+      // (the scheduling barriers keep the requests where they are written: left alone, the scheduler sinks every
+      // load next to its first use, i.e. behind the arithmetic it is meant to overlap)
+      load_block(kb, row_of(i + 1));
+      __builtin_amdgcn_sched_barrier(0);
+      process_block(ka, row_of(i), 0);
+      __builtin_amdgcn_sched_barrier(0);
+      load_block(ka, row_of(min(i + 2, n_blk - 1)));
+      __builtin_amdgcn_sched_barrier(0);
+      process_block(kb, row_of(i + 1), 1);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+  }
+
+  if (!HAS_E) return;
+  // this wave's columns of error plane tl.a: lane (li, g) holds E[k = c0 + 32 sb + 16 c + 4 g + j][s = 16 h + li]
+  float *plane = st.eout_cur + (size_t)tl.a * kMsS * st.in_pad;
+#pragma unroll
+  for (int sb = 0; sb < kMsSB; ++sb)
+#pragma unroll
+    for (int c = 0; c < 2; ++c)
+#pragma unroll
+      for (int h = 0; h < 2; ++h) {
+        float *dst = plane + (size_t)(16 * h + li) * st.in_pad + c0 + 32 * sb + 16 * c + 4 * g;
+        stg_f4(dst, make_float4(eacc[sb][c][h][0], eacc[sb][c][h][1], eacc[sb][c][h][2], eacc[sb][c][h][3]));
+      }
+}
+
+template <int MODE, int OPT>
+__global__ __launch_bounds__(64 * kMsNWM) void ms_mat_kernel(MsNet net, MsTick a) {
+  __shared__ __attribute__((aligned(16))) float zred[2][kMsNWM][1024];
+  const MsTile tl = (MODE == 0 ? net.tiles_m : net.tiles_f)[blockIdx.x];
+  const MsView st = ms_view(net.stages + tl.stage, a.cur, a.fhalf);
+  const int tid = threadIdx.x;
+  if (MODE == 0 && tl.kind == 2) {
     // a2 for the last stage: needs every output of the stage, so one work-group does it, the first of the launch.
     // Its results are released to the rest of the device before the flag is raised.
-    float *hs = &red[0][0];
+    float *hs = &zred[0][0][0];
     const MsTile whole{tl.stage, 0, st.out_pad, 0};
     switch (st.act) {
-      case PT_RELU: ms_delta_body<PT_RELU>(net, a, whole, st, hs, hs + kMsS, hs + 2 * kMsS, hs + 3 * kMsS); break;
-      case PT_GELU: ms_delta_body<PT_GELU>(net, a, whole, st, hs, hs + kMsS, hs + 2 * kMsS, hs + 3 * kMsS); break;
-      default: ms_delta_body<PT_ID>(net, a, whole, st, hs, hs + kMsS, hs + 2 * kMsS, hs + 3 * kMsS); break;
+      case PT_RELU: ms_delta_body<PT_RELU, 64 * kMsNWM>(net, a, whole, st, hs, hs + kMsS, hs + 2 * kMsS, hs + 3 * kMsS); break;
+      case PT_GELU: ms_delta_body<PT_GELU, 64 * kMsNWM>(net, a, whole, st, hs, hs + kMsS, hs + 2 * kMsS, hs + 3 * kMsS); break;
+      default: ms_delta_body<PT_ID, 64 * kMsNWM>(net, a, whole, st, hs, hs + kMsS, hs + 2 * kMsS, hs + 3 * kMsS); break;
     }
     __threadfence();
     __syncthreads();
     if (tid == 0) __hip_atomic_store(net.head_flag, a.seq, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
     return;
   }
-  if (st.is_last) {
+  if (MODE == 0 && st.is_last) {
     // delta of the last stage comes from the work-group above.  It has the lowest index of the launch, so it is
     // running or done by the time this one starts; the wait is bounded all the same, and when it runs out the
     // error flag is raised and the tile leaves the weights alone.
@@ -572,184 +830,14 @@ __global__ __launch_bounds__(256) void ms_backward_kernel(MsNet net, MsTick a) {
     // caches start a launch empty, and nobody reads the last stage's delta in this launch before the flag is up,
     // so no cache on the device can hold a line of it from before the loss head's release.
   }
-  const int row_lo = tl.a * kMsRT, row_hi = min(row_lo + kMsRT, st.out_pad);   // multiples of 32
-  const int c0 = tl.b * kMsCT;
-  const bool has_e = st.eout_cur != nullptr;
-  const bf16_t *xT = st.xT_prev ? st.xT_prev : st.xT0;
-
-  // selectors that move a 16 x 32 register block into C layout (multiplication by a 0/1 matrix is exact)
-  uint4 isel[2];
-#pragma unroll
-  for (int c = 0; c < 2; ++c) {
-    unsigned int w[4] = {0u, 0u, 0u, 0u};
-    const int m = c * 16 + li - g * 8;                 // element of this lane's 8 that must be 1.0
-    if (m >= 0 && m < 8) w[m >> 1] = (m & 1) ? 0x3f800000u : 0x00003f80u;
-    isel[c] = make_uint4(w[0], w[1], w[2], w[3]);
-  }
-  // update operand A = rnd(X)[k(slot)][s]: slot = l % 16 = 4 q + jj  ->  k = c0 + 32 sb + 8 q + 4 e + jj
-  uint4 xop[4][2];
-#pragma unroll
-  for (int sb = 0; sb < 4; ++sb)
-#pragma unroll
-    for (int e = 0; e < 2; ++e) {
-      const int k = c0 + 32 * sb + 8 * (li >> 2) + 4 * e + (li & 3);
-      xop[sb][e] = ldg16(xT + (size_t)k * kMsS + g * 8);
-    }
-  f32x4_t eacc[4][2][2];
-#pragma unroll
-  for (int sb = 0; sb < 4; ++sb)
-#pragma unroll
-    for (int c = 0; c < 2; ++c)
-#pragma unroll
-      for (int h = 0; h < 2; ++h) eacc[sb][c][h] = f32x4_t{0.f, 0.f, 0.f, 0.f};
-
-  const float scale = net.lr_over_s;
-  auto load_block = [&](uint4 (&w)[4][2], int r0) {
-#pragma unroll
-    for (int sb = 0; sb < 4; ++sb)
-#pragma unroll
-      for (int b = 0; b < 2; ++b)
-        w[sb][b] = ldg16(st.W + (size_t)(r0 + 16 * b + li) * st.in_pad + c0 + 32 * sb + g * 8);
-  };
-  auto process_block = [&](uint4 (&wreg)[4][2], int r0) {
-    // delta as B operand of E (contraction over the 32 rows): rows r0 + 16 b + 4 g + j at stream 16 h + li
-    uint4 de[2];
-#pragma unroll
-    for (int h = 0; h < 2; ++h) {
-      const bf16_t *dp = st.dlt + (size_t)(16 * h + li) * st.out_pad + r0 + 4 * g;
-      const uint2 lo = ldg8(dp), hi = ldg8(dp + 16);
-      de[h] = make_uint4(lo.x, lo.y, hi.x, hi.y);
-    }
-    // delta^T as B operand of the update (contraction over the 32 streams): row r0 + 16 b + li, streams 8 g ..
-    uint4 du[2];
-#pragma unroll
-    for (int b = 0; b < 2; ++b)
-      du[b] = ldg16(st.dltT + (size_t)(r0 + 16 * b + li) * kMsS + g * 8);
-
-    // Adam: the moments of 32 columns (both 16-row halves) travel one column group ahead of the arithmetic
-    float4 mv[OPT == 1 ? 2 : 1][2][4];
-    auto load_mv = [&](int buf, int sb) {
-#pragma unroll
-      for (int b = 0; b < 2; ++b) {
-        const size_t off = (size_t)(r0 + 16 * b + li) * st.in_pad + c0 + 32 * sb + g * 8;
-        mv[buf][b][0] = ldg_f4(st.mW + off); mv[buf][b][1] = ldg_f4(st.mW + off + 4);
-        mv[buf][b][2] = ldg_f4(st.vW + off); mv[buf][b][3] = ldg_f4(st.vW + off + 4);
-      }
-    };
-    if (OPT == 1) load_mv(0, 0);
-    __builtin_amdgcn_sched_barrier(0);   // all loads of the block are issued before the first product
-#pragma unroll
-    for (int sb = 0; sb < 4; ++sb) {
-      if (OPT == 1 && sb + 1 < 4) load_mv((sb + 1) & 1, sb + 1);
-      {
-        if (has_e) {
-          // a5: E[k][s] += sum_r W[r][k] delta[r][s] with the rows as loaded (not yet updated)
-#pragma unroll
-          for (int c = 0; c < 2; ++c) {
-            const f32x4_t z4 = {0.f, 0.f, 0.f, 0.f};
-            const f32x4_t t0 = mfma16(wreg[sb][0], isel[c], z4);   // W[r0 + 4 g + j][c0 + 32 sb + 16 c + li]
-            const f32x4_t t1 = mfma16(wreg[sb][1], isel[c], z4);   // rows + 16
-            const uint4 wt = make_uint4(pack_bf16(t0[0], t0[1]), pack_bf16(t0[2], t0[3]),
-                                        pack_bf16(t1[0], t1[1]), pack_bf16(t1[2], t1[3]));
-#pragma unroll
-            for (int h = 0; h < 2; ++h) eacc[sb][c][h] = mfma16(wt, de[h], eacc[sb][c][h]);
-          }
-        }
-        // a6: W <- rnd(W - eta/S * delta rnd(X)^T); the product comes out as lane (row li, k = 8 g + 4 e + j)
-#pragma unroll
-        for (int b = 0; b < 2; ++b) {
-          const f32x4_t z4 = {0.f, 0.f, 0.f, 0.f};
-          const f32x4_t u0 = mfma16(xop[sb][0], du[b], z4);
-          const f32x4_t u1 = mfma16(xop[sb][1], du[b], z4);
-          const uint4 w = wreg[sb][b];
-          const size_t off = (size_t)(r0 + 16 * b + li) * st.in_pad + c0 + 32 * sb + g * 8;
-          uint4 o;
-          if (OPT == 1) {
-            // Adam: the moments of the lane's 8 weights, fp32, in and out
-            const float4 m0 = mv[sb & 1][b][0], m1 = mv[sb & 1][b][1], v0 = mv[sb & 1][b][2], v1 = mv[sb & 1][b][3];
-            float wq[8] = {bf16_lo(w.x), bf16_hi(w.x), bf16_lo(w.y), bf16_hi(w.y), bf16_lo(w.z), bf16_hi(w.z), bf16_lo(w.w), bf16_hi(w.w)};
-            const float gq[8] = {u0[0], u0[1], u0[2], u0[3], u1[0], u1[1], u1[2], u1[3]};
-            float mq[8] = {m0.x, m0.y, m0.z, m0.w, m1.x, m1.y, m1.z, m1.w}, vq[8] = {v0.x, v0.y, v0.z, v0.w, v1.x, v1.y, v1.z, v1.w};
-#pragma unroll
-            for (int e = 0; e < 8; ++e) wq[e] = ms_step(net, a, wq[e], gq[e], mq[e], vq[e]);
-            stg_f4(st.mW + off, make_float4(mq[0], mq[1], mq[2], mq[3]));
-            stg_f4(st.mW + off + 4, make_float4(mq[4], mq[5], mq[6], mq[7]));
-            stg_f4(st.vW + off, make_float4(vq[0], vq[1], vq[2], vq[3]));
-            stg_f4(st.vW + off + 4, make_float4(vq[4], vq[5], vq[6], vq[7]));
-            o = make_uint4(pack_bf16(wq[0], wq[1]), pack_bf16(wq[2], wq[3]), pack_bf16(wq[4], wq[5]), pack_bf16(wq[6], wq[7]));
-          } else {
-            o.x = pack_bf16(bf16_lo(w.x) - scale * u0[0], bf16_hi(w.x) - scale * u0[1]);
-            o.y = pack_bf16(bf16_lo(w.y) - scale * u0[2], bf16_hi(w.y) - scale * u0[3]);
-            o.z = pack_bf16(bf16_lo(w.z) - scale * u1[0], bf16_hi(w.z) - scale * u1[1]);
-            o.w = pack_bf16(bf16_lo(w.w) - scale * u1[2], bf16_hi(w.w) - scale * u1[3]);
-          }
-          stg16(st.W + off, o);
-        }
-      }
-    }
-  };
-#if PT_MS_BPF
-  {
-    // two register sets: the next 32-row block is requested before the current one is worked on
-    uint4 wa[4][2], wb[4][2];
-    int r = row_lo + 32 * wv;
-    if (r < row_hi) load_block(wa, r);
-    while (r < row_hi) {
-      if (r + 128 < row_hi) load_block(wb, r + 128);
-      process_block(wa, r);
-      r += 128;
-      if (r >= row_hi) break;
-      if (r + 128 < row_hi) load_block(wa, r + 128);
-      process_block(wb, r);
-      r += 128;
-    }
-  }
-#else
-  for (int r0 = row_lo + 32 * wv; r0 < row_hi; r0 += 128) {
-    uint4 wreg[4][2];
-    load_block(wreg, r0);
-    process_block(wreg, r0);
-  }
-#endif
-
-  if (!has_e) return;
-  // add the four waves' shares in a fixed order, then wave 0 writes the tile's part of error plane tl.a
-#pragma unroll
-  for (int half = 2; half >= 1; half >>= 1) {
-    if (wv >= half && wv < 2 * half) {
-      float *dst = red[wv - half];
-#pragma unroll
-      for (int sb = 0; sb < 4; ++sb)
-#pragma unroll
-        for (int c = 0; c < 2; ++c)
-#pragma unroll
-          for (int h = 0; h < 2; ++h)
-            *reinterpret_cast<f32x4_t *>(dst + ((sb * 2 + c) * 2 + h) * 256 + lane * 4) = eacc[sb][c][h];
-    }
-    __syncthreads();
-    if (wv < half) {
-      const float *src = red[wv];
-#pragma unroll
-      for (int sb = 0; sb < 4; ++sb)
-#pragma unroll
-        for (int c = 0; c < 2; ++c)
-#pragma unroll
-          for (int h = 0; h < 2; ++h)
-            eacc[sb][c][h] += *reinterpret_cast<const f32x4_t *>(src + ((sb * 2 + c) * 2 + h) * 256 + lane * 4);
-    }
-    __syncthreads();
-  }
-  if (wv == 0) {
-    float *plane = st.eout_cur + (size_t)tl.a * kMsS * st.in_pad;
-#pragma unroll
-    for (int sb = 0; sb < 4; ++sb)
-#pragma unroll
-        for (int c = 0; c < 2; ++c)
-#pragma unroll
-          for (int h = 0; h < 2; ++h) {
-            // lane (li, g) holds E[k = c0 + 32 sb + 16 c + 4 g + j][s = 16 h + li]
-            float *dst = plane + (size_t)(16 * h + li) * st.in_pad + c0 + 32 * sb + 16 * c + 4 * g;
-            stg_f4(dst, make_float4(eacc[sb][c][h][0], eacc[sb][c][h][1], eacc[sb][c][h][2], eacc[sb][c][h][3]));
-          }
+  if (MODE == 1) {
+    ms_mat_tile<1, 0, false, true>(net, a, tl, st, zred);
+  } else if (!st.is_first) {
+    ms_mat_tile<0, OPT, true, true>(net, a, tl, st, zred);
+  } else if (a.x_next) {
+    ms_mat_tile<0, OPT, false, true>(net, a, tl, st, zred);
+  } else {
+    // the coming tick's input of the first stage is the caller's next sample: not there at the last tick of a call
+    ms_mat_tile<0, OPT, false, false>(net, a, tl, st, zred);
   }
 }

@@ -100,7 +100,7 @@ struct TickArgs {
   int cur;          // half written this tick
   int learn;        // 0 while the loss gradient is held at zero
   int rev;          // walk the rows of a tile backwards on this tick
-  int tick;         // tick number modulo 2^30 (chooses the ring slots of the skip connections)
+  int tick;         // tick number modulo a common multiple of all ring lengths (ring slots of the skip connections)
   float adam_c1;    // Adam, this tick's step n: lr / (1 - beta1^n)
   float adam_c2;    //                           1 / sqrt(1 - beta2^n)
 };
@@ -913,6 +913,8 @@ struct StageHost {
   // multi-stream path: padded sizes and its extra buffers
   int in_pad = 0, out_pad = 0, n_rt = 0;
   float *zbuf = nullptr;
+  float *zp = nullptr;               // multi-stream path: partial pre-activation planes of the coming tick [n_ct][S][out_pad]
+  int n_ct = 0;
   bf16_t *dlt = nullptr, *dltT = nullptr, *xT0 = nullptr;
   bf16_t *WTq = nullptr, *xq0 = nullptr;   // batched path: transposed weights; first stage: rnd(x(t)) [S][in_pad]
   bf16_t *xq[2] = {nullptr, nullptr}, *xT[2] = {nullptr, nullptr};   // bf16 copies of what the stage publishes
@@ -928,6 +930,9 @@ struct CvStageHost {   // one record per conv layer
   float *Wg = nullptr, *WT = nullptr, *WBT = nullptr, *b = nullptr, *delta = nullptr, *dwp = nullptr, *dbp = nullptr;
   float *mW = nullptr, *vW = nullptr, *mb = nullptr, *vb = nullptr;   // Adam moments, in the order of Wg and b
   float *act_buf[2] = {nullptr, nullptr}, *err_buf[2] = {nullptr, nullptr};
+  float *skip_ring = nullptr, *serr_ring = nullptr;   // owned by the target layer of a skip: [delay + 1][co_pad][H][W] each
+  int skip_delay = 0;                                 // stage boundaries the skip crosses
+  size_t ring_bytes = 0;
 };
 
 }  // namespace
@@ -946,6 +951,8 @@ struct partime_ctx {
   int in_dim = 0, out_dim = 0;
   float lr = 0.f;
   int64_t tick = 0;
+  int64_t ring_period = 1;              // least common multiple of the lengths of all skip rings: the kernels choose
+                                        // ring slots from the tick number modulo this
   NetDev net{};
   StageDev *d_stages = nullptr;
   TileDev *d_tiles = nullptr;
@@ -976,7 +983,11 @@ struct partime_ctx {
   MsStage *d_ms_stages = nullptr;
   MsTile *d_ms_tiles = nullptr;
   unsigned int *d_ms_head_ctr = nullptr;
-  int n_tiles_f = 0, n_tiles_b = 0;
+  int n_tiles_v = 0, n_prep = 0;        // vector launch; its first n_prep tiles round the first stage's input
+  int n_tiles_m = 0;                    // matrix launch of a learning tick (loss head first, last stage's tiles last)
+  int n_tiles_f = 0, n_tiles_f0 = 0;    // forward-only matrix launch, stage by stage; the first n_tiles_f0 are the first stage's
+  int n_tiles_i = 0;                    // inference launch
+  bool ms_zp_valid = false;             // the planes of the stages behind the first one are those of the coming tick
   // batched path (64 .. 1024 streams)
   bool rb = false;
   RbNet rbnet{};
@@ -1016,6 +1027,7 @@ void free_ctx(partime_ctx *c) {
     if (s.W) (void)hipFree(s.W);
     if (s.b) (void)hipFree(s.b);
     if (s.zbuf) (void)hipFree(s.zbuf);
+    if (s.zp) (void)hipFree(s.zp);
     if (s.dlt) (void)hipFree(s.dlt);
     if (s.dltT) (void)hipFree(s.dltT);
     if (s.xT0) (void)hipFree(s.xT0);
@@ -1040,7 +1052,7 @@ void free_ctx(partime_ctx *c) {
   if (c->d_lossp) (void)hipFree(c->d_lossp);
   if (c->d_dummy) (void)hipFree(c->d_dummy);
   for (auto &v : c->cvs) {
-    for (float *q : {v.Wg, v.WT, v.WBT, v.b, v.delta, v.dwp, v.dbp, v.act_buf[0], v.act_buf[1], v.err_buf[0], v.err_buf[1], v.out_single, v.mW, v.vW, v.mb, v.vb})
+    for (float *q : {v.Wg, v.WT, v.WBT, v.b, v.delta, v.dwp, v.dbp, v.act_buf[0], v.act_buf[1], v.err_buf[0], v.err_buf[1], v.out_single, v.mW, v.vW, v.mb, v.vb, v.skip_ring, v.serr_ring})
       if (q) (void)hipFree(q);
   }
   for (float *q : {c->hd_W, c->hd_b, c->hd_gapv, c->hd_ge[0], c->hd_ge[1], c->hd_mW, c->hd_vW, c->hd_mb, c->hd_vb})
@@ -1190,6 +1202,17 @@ int build_plan(partime_ctx *c) {
 }
 
 
+// a skip ring of n slots joins the pipeline: the tick number handed to the kernels is taken modulo a common multiple
+// of all ring lengths, so that slot = tick mod n stays right however long the stream runs
+int add_ring_length(partime_ctx *c, int n) {
+  int64_t a = c->ring_period, b = n;
+  while (b) { const int64_t r = a % b; a = b; b = r; }
+  const int64_t l = c->ring_period / a * n;
+  if (l > (int64_t)1 << 30) return fail(PT_EUNSUPPORTED, "partime_init: the delays of the skip connections have no common period below 2^30 ticks");
+  c->ring_period = l;
+  return PT_OK;
+}
+
 // ---- multi-stream path: allocation and tile lists ------------------------------------------------
 
 #define MS_TRY(expr)                                                                                   \
@@ -1210,7 +1233,7 @@ int init_multistream(partime_ctx *c, const float *const *w_host, const float *co
   const int D = c->depth, S = c->S;
   c->ms = true;
   c->stages.resize(D);
-  auto pad64 = [](int v) { return (v + 511) / 512 * 512; };   // every stage size is padded to a multiple of 512
+  auto pad512 = [](int v) { return (v + kMsTC - 1) / kMsTC * kMsTC; };   // every stage size is padded to whole column tiles
   for (int h = 0; h < D; ++h) {
     StageHost &s = c->stages[h];
     const pt_layer &l = c->layers[h];
@@ -1218,10 +1241,11 @@ int init_multistream(partime_ctx *c, const float *const *w_host, const float *co
     s.in_dim = l.in_dim;
     s.out_dim = l.out_dim;
     s.act = l.act;
-    s.in_pad = pad64(l.in_dim);
-    s.out_pad = pad64(l.out_dim);
+    s.in_pad = pad512(l.in_dim);
+    s.out_pad = pad512(l.out_dim);
     s.ld = s.in_pad;
-    s.n_rt = (s.out_pad + kMsRT - 1) / kMsRT;
+    s.n_rt = (s.out_pad + kMsTR - 1) / kMsTR;      // row tiles = error planes
+    s.n_ct = s.in_pad / kMsTC;                     // column tiles = pre-activation planes
     s.n_parts = s.n_rt;
     s.act_elems = (size_t)S * s.out_pad;
     s.err_elems = (size_t)s.n_rt * S * s.in_pad;
@@ -1238,10 +1262,11 @@ int init_multistream(partime_ctx *c, const float *const *w_host, const float *co
       if ((rc = alloc_zero(&s.mW, nw)) != PT_OK || (rc = alloc_zero(&s.vW, nw)) != PT_OK) return rc;
       if ((rc = alloc_zero(&s.mb, (size_t)s.out_pad)) != PT_OK || (rc = alloc_zero(&s.vb, (size_t)s.out_pad)) != PT_OK) return rc;
     }
-    if ((rc = alloc_zero(&s.zbuf, s.act_elems)) != PT_OK) return rc;
+    if ((rc = alloc_zero(&s.zp, (size_t)s.n_ct * s.act_elems)) != PT_OK) return rc;
+    if (h == D - 1 && (rc = alloc_zero(&s.zbuf, s.act_elems)) != PT_OK) return rc;
     if ((rc = alloc_zero(&s.dlt, s.act_elems)) != PT_OK) return rc;
     if ((rc = alloc_zero(&s.dltT, s.act_elems)) != PT_OK) return rc;
-    if (h == 0 && (rc = alloc_zero(&s.xT0, (size_t)s.in_pad * S)) != PT_OK) return rc;
+    if (h == 0 && ((rc = alloc_zero(&s.xT0, (size_t)s.in_pad * S)) != PT_OK || (rc = alloc_zero(&s.xq0, (size_t)s.in_pad * S)) != PT_OK)) return rc;
     for (int p = 0; p < 2; ++p) {
       if (h < D - 1 && (rc = alloc_zero(&s.act_buf[p], s.act_elems)) != PT_OK) return rc;
       if (h < D - 1 && (rc = alloc_zero(&s.xq[p], s.act_elems)) != PT_OK) return rc;
@@ -1251,7 +1276,9 @@ int init_multistream(partime_ctx *c, const float *const *w_host, const float *co
     if ((rc = upload_weights(c, h, w_host[h], b_host[h])) != PT_OK) return rc;
   }
   std::vector<MsStage> sd(D);
-  std::vector<MsTile> tf, tb, tb_last;
+  std::vector<MsTile> tv, tm, tm_last, tf, ti;
+  for (int k0 = 0; k0 < c->stages[0].in_pad; k0 += kMsVR) tv.push_back(MsTile{0, k0, 0, 1});   // the input of the first stage
+  c->n_prep = (int)tv.size();
   for (int h = 0; h < D; ++h) {
     StageHost &s = c->stages[h];
     MsStage &d = sd[h];
@@ -1260,10 +1287,10 @@ int init_multistream(partime_ctx *c, const float *const *w_host, const float *co
     d.b = s.b;
     d.mW = s.mW; d.vW = s.vW; d.mb = s.mb; d.vb = s.vb;
     d.in_dim = s.in_dim; d.out_dim = s.out_dim; d.in_pad = s.in_pad; d.out_pad = s.out_pad;
-    d.act = s.act; d.is_last = h == D - 1;
-    d.zbuf = s.zbuf; d.dlt = s.dlt; d.dltT = s.dltT; d.xT0 = s.xT0;
+    d.act = s.act; d.is_last = h == D - 1; d.is_first = h == 0;
+    d.zp = s.zp; d.n_ct = s.n_ct;
+    d.zbuf = s.zbuf; d.dlt = s.dlt; d.dltT = s.dltT; d.xT0 = s.xT0; d.xq0 = s.xq0;
     for (int p = 0; p < 2; ++p) {
-      d.in_act[p] = h > 0 ? c->stages[h - 1].act_buf[p] : nullptr;
       d.out_act[p] = s.act_buf[p];
       d.xq_in[p] = h > 0 ? c->stages[h - 1].xq[p] : nullptr;
       d.xq_out[p] = s.xq[p];
@@ -1274,29 +1301,37 @@ int init_multistream(partime_ctx *c, const float *const *w_host, const float *co
     }
     d.n_gparts = h < D - 1 ? c->stages[h + 1].n_rt : 0;
     d.n_rt = s.n_rt;
-    for (int r = 0; r < s.out_pad; r += kMsRowsF) tf.push_back(MsTile{h, r, kMsRowsF, 0});
-    std::vector<MsTile> &dst = h == D - 1 ? tb_last : tb;
+    for (int r = 0; r < s.out_pad; r += kMsVR) tv.push_back(MsTile{h, r, 0, 0});
+    for (int r = 0; r < s.out_pad; r += kMsRowsF) ti.push_back(MsTile{h, r, kMsRowsF, 0});
+    std::vector<MsTile> &dst = h == D - 1 ? tm_last : tm;
     for (int p = 0; p < s.n_rt; ++p)
-      for (int q = 0; q < (s.in_pad + kMsCT - 1) / kMsCT; ++q) dst.push_back(MsTile{h, p, q, 0});
+      for (int q = 0; q < s.n_ct; ++q) {
+        dst.push_back(MsTile{h, p, q, 0});
+        tf.push_back(MsTile{h, p, q, 0});
+      }
+    if (h == 0) c->n_tiles_f0 = (int)tf.size();
   }
-  // backward launch: the loss head of the last stage first, then the other stages walking the weights in the
-  // opposite direction to the forward launch (what either one touched last is what the other touches first,
-  // while it is still in the last-level cache), then the last stage, whose delta the loss head provides
-  if (c->serpentine) std::reverse(tb.begin(), tb.end());
-  c->msnet.sweep = c->serpentine != 0;
-  tb.insert(tb.begin(), MsTile{D - 1, 0, 0, 2});
-  tb.insert(tb.end(), tb_last.begin(), tb_last.end());
+  // matrix launch of a learning tick: the loss head of the last stage first, the last stage's own tiles (which wait
+  // for the delta it provides) last
+  tm.insert(tm.begin(), MsTile{D - 1, 0, 0, 2});
+  tm.insert(tm.end(), tm_last.begin(), tm_last.end());
+  c->n_tiles_v = (int)tv.size();
+  c->n_tiles_m = (int)tm.size();
   c->n_tiles_f = (int)tf.size();
-  c->n_tiles_b = (int)tb.size();
-  std::vector<MsTile> all(tf);
-  all.insert(all.end(), tb.begin(), tb.end());
+  c->n_tiles_i = (int)ti.size();
+  std::vector<MsTile> all(tv);
+  all.insert(all.end(), tm.begin(), tm.end());
+  all.insert(all.end(), tf.begin(), tf.end());
+  all.insert(all.end(), ti.begin(), ti.end());
   MS_TRY(hipMalloc(reinterpret_cast<void **>(&c->d_ms_stages), sizeof(MsStage) * D));
   MS_TRY(hipMemcpy(c->d_ms_stages, sd.data(), sizeof(MsStage) * D, hipMemcpyHostToDevice));
   MS_TRY(hipMalloc(reinterpret_cast<void **>(&c->d_ms_tiles), sizeof(MsTile) * all.size()));
   MS_TRY(hipMemcpy(c->d_ms_tiles, all.data(), sizeof(MsTile) * all.size(), hipMemcpyHostToDevice));
   c->msnet.stages = c->d_ms_stages;
-  c->msnet.tiles_f = c->d_ms_tiles;
-  c->msnet.tiles_b = c->d_ms_tiles + tf.size();
+  c->msnet.tiles_v = c->d_ms_tiles;
+  c->msnet.tiles_m = c->d_ms_tiles + tv.size();
+  c->msnet.tiles_f = c->d_ms_tiles + tv.size() + tm.size();
+  c->msnet.tiles_i = c->d_ms_tiles + tv.size() + tm.size() + tf.size();
   c->msnet.loss = c->cfg.loss;
   c->msnet.out_dim = c->out_dim;
   c->msnet.lr_over_s = c->lr / (float)S;
@@ -1312,6 +1347,7 @@ int init_multistream(partime_ctx *c, const float *const *w_host, const float *co
     if ((rc = alloc_zero(&c->d_hist[p], std::max<size_t>(1, (size_t)c->k) * c->tgt_bytes)) != PT_OK) return rc;
   if ((rc = alloc_zero(&c->d_err, 1)) != PT_OK) return rc;
   c->msnet.err = c->d_err;
+  c->ms_zp_valid = false;
   MS_TRY(hipDeviceSynchronize());
   return PT_OK;
 }
@@ -1371,6 +1407,7 @@ int init_batched(partime_ctx *c, const float *const *w_host, const float *const 
       const size_t n = (size_t)(s.skip_delay + 1) * S * s.out_pad;
       s.ring_bytes = n * 4;
       if ((rc = alloc_zero(&s.skip_ring, n)) != PT_OK || (rc = alloc_zero(&s.serr_ring, n)) != PT_OK) return rc;
+      if ((rc = add_ring_length(c, s.skip_delay + 1)) != PT_OK) return rc;
     }
     if ((rc = upload_weights(c, h, w_host[h], b_host[h])) != PT_OK) return rc;
   }
@@ -1597,6 +1634,8 @@ int init_conv(partime_ctx *c, const float *const *w_host, const float *const *b_
       return fail(PT_EUNSUPPORTED, "partime_init: layer %d: conv stages are 3x3 with at most %d channels in and out, one frame size", h, kCvMaxC);
     if (h > 0 && l.c_in != c->layers[h - 1].c_out)
       return fail(PT_ESHAPE, "partime_init: layer %d takes %d channels, layer %d gives %d", h, l.c_in, h - 1, c->layers[h - 1].c_out);
+    if (l.skip_from >= 0 && c->layers[l.skip_from].c_out != l.c_out)
+      return fail(PT_ESHAPE, "partime_init: layer %d adds the output of layer %d: %d channels != %d", h, l.skip_from, l.c_out, c->layers[l.skip_from].c_out);
   }
   c->cv = true;
   c->in_dim = c->layers[0].c_in * HW;
@@ -1636,6 +1675,14 @@ int init_conv(partime_ctx *c, const float *const *w_host, const float *const *b_
                  (rc = alloc_zero(&v.vb, (size_t)v.co_pad))))
       return rc;
     if (v.pos < v.cnt - 1 && (rc = alloc_zero(&v.out_single, (size_t)v.co_pad * HW))) return rc;
+    if (c->layers[h].skip_from >= 0) {
+      // target of a skip: the rings of the skipped map and of its gradient, one frame per tick of delay and one more
+      v.skip_delay = v.stage - c->cvs[c->layers[h].skip_from].stage;
+      const size_t n = (size_t)(v.skip_delay + 1) * v.co_pad * HW;
+      v.ring_bytes = n * 4;
+      if ((rc = alloc_zero(&v.skip_ring, n)) || (rc = alloc_zero(&v.serr_ring, n))) return rc;
+      if ((rc = add_ring_length(c, v.skip_delay + 1)) != PT_OK) return rc;
+    }
     for (int p = 0; p < 2; ++p) {
       if (v.pos == v.cnt - 1 && (rc = alloc_zero(&v.act_buf[p], (size_t)v.co_pad * HW))) return rc;
       if (v.pos == 0 && v.stage > 0 && (rc = alloc_zero(&v.err_buf[p], (size_t)v.ci_pad * HW))) return rc;
@@ -1669,6 +1716,14 @@ int init_conv(partime_ctx *c, const float *const *w_host, const float *const *b_
     d.pred_delta = first ? nullptr : c->cvs[h - 1].delta;
     d.pred_dbp = first ? nullptr : c->cvs[h - 1].dbp;
     d.pred_act = first ? PT_ID : c->cvs[h - 1].act;
+    if (v.skip_ring) {
+      d.skip_in = v.skip_ring; d.serr_out = v.serr_ring; d.skip_n = v.skip_delay + 1; d.skip_d = v.skip_delay;
+    }
+    for (int t = h + 1; t < n_conv; ++t)
+      if (c->layers[t].skip_from == h) {   // this layer's output is skipped to layer t
+        const CvStageHost &q = c->cvs[t];
+        d.skip_out = q.skip_ring; d.serr_in = q.serr_ring; d.src_n = q.skip_delay + 1; d.src_d = q.skip_delay;
+      }
     for (int p = 0; p < 2; ++p) {
       d.in_act[p] = h == 0 ? nullptr : (first ? c->cvs[h - 1].act_buf[p] : c->cvs[h - 1].out_single);
       d.out_act[p] = last ? v.act_buf[p] : v.out_single;
@@ -1783,10 +1838,10 @@ int partime_init(const partime_config *cfg, const float *const *w_host, const fl
     const int sf = cfg->layers[i].skip_from;
     if (sf < -1 || sf >= i) return fail(PT_EINVAL, "partime_init: layer %d: skip_from must name an earlier layer or be -1", i);
     if (sf < 0) continue;
-    if (any_conv || (cfg->n_streams != 1 && cfg->n_streams < 64) || cfg->exec_mode == PT_EXEC_PERSISTENT)
-      return fail(PT_EUNSUPPORTED, "partime_init: skip connections are built for dense pipelines of one stream or of 64 and more, launch per tick");
+    if ((cfg->n_streams != 1 && cfg->n_streams < 64) || cfg->exec_mode == PT_EXEC_PERSISTENT)
+      return fail(PT_EUNSUPPORTED, "partime_init: skip connections are built for pipelines of one stream or of 64 and more, launch per tick");
     if (i == cfg->n_layers - 1) return fail(PT_EUNSUPPORTED, "partime_init: the last layer cannot be the target of a skip");
-    if (cfg->layers[sf].out_dim != cfg->layers[i].out_dim)
+    if (!any_conv && cfg->layers[sf].out_dim != cfg->layers[i].out_dim)
       return fail(PT_ESHAPE, "partime_init: layer %d adds the output of layer %d: %d != %d", i, sf, cfg->layers[i].out_dim, cfg->layers[sf].out_dim);
     for (int q = 0; q < i; ++q)
       if (cfg->layers[q].skip_from == sf) return fail(PT_EUNSUPPORTED, "partime_init: layer %d is the source of two skips", sf);
@@ -1957,6 +2012,7 @@ int partime_init(const partime_config *cfg, const float *const *w_host, const fl
         INIT_TRY(hipMalloc(q, n * 4));
         INIT_TRY(hipMemset(*q, 0, n * 4));
       }
+      if ((rc = add_ring_length(c, s.skip_delay + 1)) != PT_OK) return bail(rc);
     }
     rc = upload_weights(c, h, w_host[h], b_host[h]);
     if (rc != PT_OK) return bail(rc);
@@ -2092,6 +2148,7 @@ static int run_ticks(partime_ctx *c, const float *x_dev, const void *target_dev,
       a.x = x_dev + (size_t)i * c->in_dim;
       a.out = out_dev + (size_t)i * c->out_dim;
       a.cur = (int)(t & 1);
+      a.tick = (int)(t % c->ring_period);
       a.adam_c1 = a.adam_c2 = 0.f;
       if (c->cfg.optimizer == PT_OPT_ADAM) {
         const double n = (double)(t + 1);
@@ -2147,7 +2204,7 @@ static int run_ticks(partime_ctx *c, const float *x_dev, const void *target_dev,
         a.tgt = i >= c->k ? tgt + (size_t)(i - c->k) * c->tgt_bytes
                           : c->d_hist[c->hist_cur] + (size_t)i * c->tgt_bytes;
       a.loss1 = loss_dev ? loss_dev + i : c->d_dummy;
-      a.tick = (int)(t & 0x3fffffff);
+      a.tick = (int)(t % c->ring_period);
       a.adam_c1 = a.adam_c2 = 0.f;
       if (c->cfg.optimizer == PT_OPT_ADAM) {
         const double n = (double)(t + 1);
@@ -2182,13 +2239,29 @@ static int run_ticks(partime_ctx *c, const float *x_dev, const void *target_dev,
     }
     HIP_TRY(hipGetLastError());
   } else if (c->ms) {
-    // multi-stream path: forward (with the delta epilogue) and backward launches per tick
+    // multi-stream path.  A learning tick is a vector launch and a matrix launch; the matrix launch of tick t also forms
+    // the pre-activation planes of tick t + 1.  What it could not form (the first stage's at the last tick of the previous
+    // call: the caller's next sample was not known; everything after inference ticks or after the state was changed from
+    // outside) is formed here first by a forward-only matrix launch.  An inference tick is one launch of its own kernel.
+    if (learn) {
+      MsTick a{};
+      a.x = x_dev;
+      a.x_next = x_dev;                       // the prep tiles round "the coming tick's" samples: here this tick's
+      a.cur = (int)(c->tick & 1);
+      a.fhalf = a.cur ^ 1;                    // inputs of tick t are what the stages published at tick t - 1
+      hipLaunchKernelGGL(ms_vec_kernel<false>, dim3(c->n_prep), dim3(256), 0, c->stream, c->msnet, a);
+      const int nf = c->ms_zp_valid ? c->n_tiles_f0 : c->n_tiles_f;
+      hipLaunchKernelGGL((ms_mat_kernel<1, 0>), dim3(nf), dim3(64 * kMsNWM), 0, c->stream, c->msnet, a);
+      c->last_launches += 2;
+    }
     for (int i = 0; i < n_ticks; ++i) {
       const int64_t t = c->tick + i;
-      MsTick a;
+      MsTick a{};
       a.x = x_dev + (size_t)i * c->S * c->in_dim;
+      a.x_next = i + 1 < n_ticks ? a.x + (size_t)c->S * c->in_dim : nullptr;
       a.out = out_dev + (size_t)i * c->S * c->out_dim;
       a.cur = (int)(t & 1);
+      a.fhalf = a.cur;                        // inputs of tick t + 1 are what the stages publish in this tick
       a.learn = learn && t >= c->fill && c->cfg.loss != PT_LOSS_NONE;
       a.tgt = nullptr;
       if (learn && c->cfg.loss != PT_LOSS_NONE)
@@ -2203,17 +2276,18 @@ static int run_ticks(partime_ctx *c, const float *x_dev, const void *target_dev,
         a.adam_c2 = (float)(1.0 / std::sqrt(1.0 - std::pow((double)c->cfg.beta2, n)));
       }
       if (learn) {
-        hipLaunchKernelGGL(ms_forward_kernel<true>, dim3(c->n_tiles_f), dim3(256), 0, c->stream, c->msnet, a);
+        hipLaunchKernelGGL(ms_vec_kernel<true>, dim3(c->n_tiles_v), dim3(256), 0, c->stream, c->msnet, a);
         if (c->cfg.optimizer == PT_OPT_ADAM)
-          hipLaunchKernelGGL(ms_backward_kernel<1>, dim3(c->n_tiles_b), dim3(256), 0, c->stream, c->msnet, a);
+          hipLaunchKernelGGL((ms_mat_kernel<0, 1>), dim3(c->n_tiles_m), dim3(64 * kMsNWM), 0, c->stream, c->msnet, a);
         else
-          hipLaunchKernelGGL(ms_backward_kernel<0>, dim3(c->n_tiles_b), dim3(256), 0, c->stream, c->msnet, a);
+          hipLaunchKernelGGL((ms_mat_kernel<0, 0>), dim3(c->n_tiles_m), dim3(64 * kMsNWM), 0, c->stream, c->msnet, a);
         c->last_launches += 2;
       } else {
-        hipLaunchKernelGGL(ms_forward_kernel<false>, dim3(c->n_tiles_f), dim3(256), 0, c->stream, c->msnet, a);
+        hipLaunchKernelGGL(ms_infer_kernel, dim3(c->n_tiles_i), dim3(256), 0, c->stream, c->msnet, a);
         c->last_launches += 1;
       }
     }
+    c->ms_zp_valid = learn;   // (an inference tick forms no planes for the tick after it)
     HIP_TRY(hipGetLastError());
   } else
   for (int base = 0; base < n_ticks; base += kLossSlots) {
@@ -2258,7 +2332,7 @@ static int run_ticks(partime_ctx *c, const float *x_dev, const void *target_dev,
       a.out = out_dev + (size_t)i * c->S * c->out_dim;
       a.cur = (int)(t & 1);
       a.rev = c->serpentine ? (int)(t & 1) : 0;
-      a.tick = (int)(t & 0x3fffffff);
+      a.tick = (int)(t % c->ring_period);
       a.learn = learn && t >= c->fill && c->cfg.loss != PT_LOSS_NONE;
       a.tgt = nullptr;
       if (learn && c->cfg.loss != PT_LOSS_NONE)
@@ -2413,6 +2487,7 @@ int partime_set_state(partime_ctx *ctx, int layer, const float *w_host, const fl
   if (!ctx) return fail(PT_EINVAL, "partime_set_state: null context");
   if (layer < 0 || layer >= (int)ctx->layers.size()) return fail(PT_EINVAL, "partime_set_state: layer %d out of range", layer);
   HIP_TRY(hipStreamSynchronize(ctx->stream));
+  ctx->ms_zp_valid = false;   // (32 streams: the pre-activation planes formed ahead of the coming tick are stale now)
   if (ctx->cv) return cv_upload(ctx, layer, w_host, b_host);
   return upload_weights(ctx, layer, w_host, b_host);
 }
@@ -2510,6 +2585,7 @@ int partime_set_buffer(partime_ctx *ctx, int which, int stage, int half, const f
   int rc = buffer_args(ctx, which, stage, half, host, "partime_set_buffer");
   if (rc != PT_OK) return rc;
   HIP_TRY(hipStreamSynchronize(ctx->stream));
+  ctx->ms_zp_valid = false;
   if (which == 2) {
     if (ctx->k > 0 && ctx->cfg.loss != PT_LOSS_NONE)
       HIP_TRY(hipMemcpy(ctx->d_hist[ctx->hist_cur], host, (size_t)ctx->k * ctx->tgt_bytes, hipMemcpyHostToDevice));
@@ -2599,6 +2675,7 @@ int partime_set_tick(partime_ctx *ctx, int64_t tick) {
     HIP_TRY(hipMemset(ctx->d_ms_head_ctr, 0, sizeof(unsigned int)));
   }
   ctx->tick = tick;
+  ctx->ms_zp_valid = false;   // which half of the published activations feeds the coming tick depends on its parity
   return PT_OK;
 }
 
@@ -2620,6 +2697,11 @@ int partime_reset(partime_ctx *ctx) {
     for (int p = 0; p < 2; ++p) {
       if (v.act_buf[p]) HIP_TRY(hipMemset(v.act_buf[p], 0, (size_t)v.co_pad * v.H * v.W * 4));
       if (v.err_buf[p]) HIP_TRY(hipMemset(v.err_buf[p], 0, (size_t)v.ci_pad * v.H * v.W * 4));
+    }
+  for (auto &v : ctx->cvs)
+    if (v.skip_ring) {
+      HIP_TRY(hipMemset(v.skip_ring, 0, v.ring_bytes));
+      HIP_TRY(hipMemset(v.serr_ring, 0, v.ring_bytes));
     }
   if (ctx->cv)
     for (int p = 0; p < 2; ++p) HIP_TRY(hipMemset(ctx->hd_ge[p], 0, (size_t)ctx->cvs.back().co_pad * 4));
@@ -2661,6 +2743,7 @@ int partime_reset(partime_ctx *ctx) {
   for (int p = 0; p < 2; ++p)
     HIP_TRY(hipMemset(ctx->d_hist[p], 0, std::max<size_t>(1, (size_t)ctx->k) * ctx->tgt_bytes));
   ctx->tick = 0;
+  ctx->ms_zp_valid = false;
   return PT_OK;
 }
 

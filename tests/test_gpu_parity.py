@@ -350,6 +350,41 @@ def test_multistream_chunked_infer_and_state():
     p.close()
 
 
+def test_multistream_inference_between_learning_calls():
+    """A learning tick of the 32-stream path leaves the next tick's pre-activations behind; inference ticks take a kernel
+    of their own and leave none.  Learning, inference and learning again, partly in one-tick calls, must follow the
+    oracle through every switch."""
+    w = ms_workload([96, 1100, 600, 10], ps.ACT_GELU, ps.LOSS_CE, lr=0.05, drift=0.05, seed=61)
+    Ws, bs = ps.init_weights(w.layers, w.seed)
+    x, tg = ps.make_inputs(w, 40)
+    ref = orc.Oracle(w.layers, Ws, bs, loss=w.loss, lr=w.lr, n_streams=32, w_bf16=True, operands_bf16=True)
+    p = Pipeline(w.layers, Ws, bs, loss=w.loss, lr=w.lr, n_streams=32, w_dtype=B.PT_BF16)
+    xd, td = torch.from_numpy(x).cuda(), torch.from_numpy(tg).cuda()
+    D = w.depth
+    t = 0
+    for kind, n in [("L", 9), ("I", 1), ("L", 1), ("L", 1), ("I", 6), ("I", 1), ("L", 7), ("I", 3), ("L", 11)]:
+        if kind == "L":
+            ro, rl = ref.step(x[t:t + n], tg[t:t + n])
+            o, l = p.step(xd[t:t + n], td[t:t + n])
+            for i in range(n):
+                if t + i >= D - 1:
+                    assert abs(float(l[i]) - rl[i]) <= 10 * BF16_TOL * max(abs(rl[i]), 1e-3), (t + i, float(l[i]), rl[i])
+        else:
+            ro = ref.infer(x[t:t + n])
+            o = p.infer(xd[t:t + n])
+        o = o.cpu().numpy()
+        for i in range(n):
+            if t + i >= D - 1:
+                assert rel(o[i], ro[i]) < BF16_TOL, (kind, t + i, rel(o[i], ro[i]))
+        t += n
+    for i in range(len(w.layers)):
+        W, b = p.weights(i)
+        W0, b0 = ref.get_weights(i)
+        assert rel(W, W0) < BF16_TOL and rel(b, b0) < BF16_TOL
+        assert rel(W - Ws[i], W0 - Ws[i]) < 5 * BF16_TOL, (i, rel(W - Ws[i], W0 - Ws[i]))
+    p.close()
+
+
 @pytest.mark.parametrize("loss", [ps.LOSS_CE, ps.LOSS_MSE])
 def test_multistream_adam(loss):
     # 32 streams with Adam: moments of the weights (updated in the backward launch) and of the biases (forward epilogue,
@@ -868,3 +903,57 @@ def test_inference_bf16_between_learning_calls():
 def test_skip_connections_wide_full_rows():
     w = skip_workload([4096, 4096, 4096, 4096, 64], {2: 0}, ps.ACT_GELU, ps.LOSS_MSE, lr=0.02, drift=0.01, seed=43)
     run_pair(w, 12, min_move=1e-3)
+
+
+# ----------------------------------------------------------------------------- residual connections between conv layers (Sec. V-C)
+
+def conv_skip_workload(h, w, n_conv, feat, skips, act=ps.ACT_GELU, loss=ps.LOSS_CE, n_classes=6, **kw):
+    layers = ps.conv_net(3, h, w, n_conv, n_classes, act=act, feat=feat)
+    for dst, src in skips.items():
+        layers[dst].skip_from = src
+    return ps.Workload(f"cnn{n_conv}_{h}x{w}_skip", layers, loss=loss, n_classes=n_classes if loss == ps.LOSS_CE else 0, **kw)
+
+
+@pytest.mark.parametrize("balance", [None, [6, 1], [2, 2, 2, 1], [1, 3, 2, 1], [3, 1, 1, 1, 1]])
+@pytest.mark.parametrize("loss", [ps.LOSS_MSE, ps.LOSS_CE])
+def test_conv_skip_connections(balance, loss):
+    """Residual connections between feature maps: inside a stage, to the next stage and across several stages (a
+    two-conv block that crosses a stage boundary among them); layer 2 is target of one skip and source of another.
+    The skipped map and its gradient wait in rings of frames as long as the stages they cross.  37 channels: the last
+    channel block is ragged."""
+    wl = conv_skip_workload(16, 32, 6, 37, {2: 0, 4: 1, 3: 2}, loss=loss, lr=0.05, seed=71, balance=balance)
+    run_pair(wl, 24, tol=CONV_TOL, min_move=1e-4)
+    if loss == ps.LOSS_CE:
+        run_pair(wl, 24, tol=CONV_TOL, chunks=[(0, 1), (1, 2), (2, 3), (3, 13), (13, 24)], k=0)
+    if balance == [1, 3, 2, 1] and loss == ps.LOSS_MSE:
+        assert_sees_updates(wl, 20, tol=CONV_TOL)
+
+
+@pytest.mark.parametrize("feat,h,w", [(64, 8, 64), (130, 2, 128), (64, 2, 256)])
+def test_conv_skip_connections_full_blocks_adam_and_infer(feat, h, w):
+    """Whole blocks of 64 channels (and three of them), the wider frame kernels, Adam, and inference with ReLU."""
+    wl = conv_skip_workload(h, w, 4, feat, {2: 0, 3: 1}, loss=ps.LOSS_CE, lr=1e-3, seed=72, balance=[1, 2, 1, 1])
+    run_pair(wl, 16, tol=CONV_TOL, adam=ADAM, min_move=2e-4)
+    for l in wl.layers[:-1]:
+        l.act = ps.ACT_RELU
+    Ws, bs = ps.init_weights(wl.layers, wl.seed)
+    x, _ = ps.make_inputs(wl, 8)
+    ref = orc.Oracle(wl.layers, Ws, bs, loss=wl.loss, lr=wl.lr, balance=wl.balance)
+    p = Pipeline(wl.layers, Ws, bs, loss=wl.loss, lr=wl.lr, balance=wl.balance)
+    ro = ref.infer(x)
+    out = p.infer(torch.from_numpy(x).cuda()).cpu().numpy()
+    assert max(rel(out[t], ro[t]) for t in range(wl.depth - 1, 8)) < CONV_TOL
+    # without the residual adds the output is another one: the comparison above sees them
+    plain = [ps.LayerSpec(l.kind, l.act, l.in_dim, l.out_dim, l.c_in, l.c_out, l.h, l.w) for l in wl.layers]
+    r0 = orc.Oracle(plain, Ws, bs, loss=wl.loss, lr=wl.lr, balance=wl.balance).infer(x)
+    assert rel(r0[7], ro[7]) > 100 * CONV_TOL
+    p.close()
+
+
+def test_conv_skip_refusals():
+    wl = conv_skip_workload(8, 32, 3, 16, {2: 0})
+    wl.layers[2].c_out = 24
+    wl.layers[3].c_in = 24                       # the head takes what layer 2 gives; layer 2 cannot add 16 channels to its 24
+    Ws, bs = ps.init_weights(wl.layers, 1)
+    with pytest.raises(B.PartimeError):
+        Pipeline(wl.layers, Ws, bs, loss=wl.loss, lr=wl.lr)
