@@ -89,6 +89,13 @@ struct NetDev {
   int depth, n_tiles, loss, out_dim, xs_len, red_len, max_rows;
   float lr;
   float beta1, beta2, eps;   // Adam
+  // softmax head split over several tiles: where the tiles leave their outputs for each other, the counter of tiles
+  // that have done so (monotonic over the ticks), how long a tile may wait for the others, the flag it raises if not
+  float *head_o;
+  unsigned int *head_ctr;
+  int *err;
+  long long spin_limit;
+  int head_parts;            // tiles of the softmax head (1: it keeps its outputs to itself, nothing is exchanged)
 };
 
 struct TickArgs {
@@ -101,6 +108,7 @@ struct TickArgs {
   int learn;        // 0 while the loss gradient is held at zero
   int rev;          // walk the rows of a tile backwards on this tick
   int tick;         // tick number modulo a common multiple of all ring lengths (ring slots of the skip connections)
+  unsigned int head_target;   // value of the head counter once every tile of the softmax head has published its outputs
   float adam_c1;    // Adam, this tick's step n: lr / (1 - beta1^n)
   float adam_c2;    //                           1 / sqrt(1 - beta2^n)
 };
@@ -117,6 +125,7 @@ struct BlockArgs {
   unsigned long long *bar;    // arrival counter of the grid barrier (monotonic)
   int *err;                   // set when a barrier wait ran out
   unsigned long long bar_base;
+  unsigned int head_base, head_parts;   // head counter before the block; tiles of the softmax head
   long long t0, spin_limit;
   int n_ticks, fill, k, serp, has_loss, pl, tgt_bytes, in_stride, out_stride;
 };
@@ -440,26 +449,63 @@ __device__ __forceinline__ void run_tile(const NetDev &net, const StageView &st,
   }
 
   if (ce_head) {
-    // softmax needs every output of the stage before any delta exists: a forward-only pass first
+    // softmax needs every output of the stage before any delta exists: a forward-only pass over this tile's rows first
+    // (the learning pass below then finds them in the cache); the tiles of the stage leave their outputs for each other
+    // in memory and each one waits until all have done so.  The head's tiles are the first of the launch and a launch
+    // is one round of work-groups, so they are all running; the wait is bounded all the same, and when it runs out the
+    // error flag is raised and the tile leaves the weights alone.
+    __shared__ int s_head_ok;
+    const bool xchg = net.head_parts > 1;
+    const int n_all = st.out_dim;
+    float *oall = red;
     for (int g0 = wv * RB; g0 < nrows; g0 += NW * RB) {
       load_rows<WT, NCH, RB>(R[0], W, ld, row0 + g0, row_end, lane);
       float acc[RB];
       dot_rows<WT, NCH, RB>(R[0], xs, lane, acc);
 #pragma unroll
       for (int rb = 0; rb < RB; ++rb)
-        if (g0 + rb < nrows && lane == 0) ov[g0 + rb] = act_fwd(st.act, acc[rb] + bsh[g0 + rb]);
+        if (g0 + rb < nrows && lane == 0) {
+          const float o = act_fwd(st.act, acc[rb] + bsh[g0 + rb]);
+          if (xchg) st_x<true>(net.head_o + row0 + g0 + rb, o);
+          else oall[g0 + rb] = o;
+        }
     }
+    // every wave waits until its own stores have been acknowledged, then the work-group announces itself
+    if (xchg) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
+    if (xchg && tid == 0) {
+      __hip_atomic_fetch_add(net.head_ctr, 1u, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
+      long long spins = 0;
+      int ok = 1;
+      while ((int)(__hip_atomic_load(net.head_ctr, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_AGENT) - a.head_target) < 0) {
+        __builtin_amdgcn_s_sleep(1);
+        if (++spins > net.spin_limit) {
+          __hip_atomic_store(net.err, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+          ok = 0;
+          break;
+        }
+      }
+      s_head_ok = ok;
+    }
+    if (xchg) {
+      __syncthreads();
+      if (!s_head_ok) return;
+    }
+    // all outputs of the stage, the same in every tile and summed in the same order: the tiles agree bit for bit
     float m = -INFINITY;
-    for (int i = tid; i < nrows; i += NT) m = fmaxf(m, ov[i]);
+    for (int i = tid; i < n_all; i += NT) {
+      const float v = xchg ? ld_x<true>(net.head_o + i) : oall[i];
+      if (xchg) oall[i] = v;
+      m = fmaxf(m, v);
+    }
     m = block_max<NW>(m, sm);
     float s = 0.f;
-    for (int i = tid; i < nrows; i += NT) s += expf(ov[i] - m);
+    for (int i = tid; i < n_all; i += NT) s += expf(oall[i] - m);
     s = block_sum<NW>(s, sm + NW);
-    const int y = min(max(static_cast<const int *>(a.tgt)[0], 0), nrows - 1);  // class id, kept in range
+    const int y = min(max(static_cast<const int *>(a.tgt)[0], 0), n_all - 1);  // class id, kept in range
     for (int i = tid; i < nrows; i += NT)
-      gs[i] = a.learn ? expf(ov[i] - m) / s - (i == y ? 1.f : 0.f) : 0.f;
-    if (tid == 0) a.loss1[0] = a.learn ? -(ov[y] - m - logf(s)) : 0.f;
+      gs[i] = a.learn ? expf(oall[row0 + i] - m) / s - (row0 + i == y ? 1.f : 0.f) : 0.f;
+    if (tid == 0 && tl.part == 0) a.loss1[0] = a.learn ? -(oall[y] - m - logf(s)) : 0.f;
     __syncthreads();
 #pragma unroll
     for (int b = 0; b < NBUF; ++b)
@@ -755,6 +801,7 @@ __global__ __launch_bounds__(NW * 64) void persistent_kernel(NetDev net, BlockAr
     a.cur = (int)(t & 1);
     a.rev = pa.serp ? (int)(t & 1) : 0;
     a.tick = (int)(t & 0x3fffffff);
+    a.head_target = pa.head_base + (unsigned int)(i + 1) * pa.head_parts;
     a.adam_c1 = a.adam_c2 = 0.f;
     a.learn = LEARN && pa.has_loss && t >= pa.fill;
     a.tgt = i >= pa.k ? pa.tgt + (size_t)(i - pa.k) * pa.tgt_bytes : pa.hist + (size_t)i * pa.tgt_bytes;
@@ -974,6 +1021,10 @@ struct partime_ctx {
   int max_grid = 0;                     // co-resident work-groups of the persistent kernels
   unsigned long long *d_bar = nullptr;  // barrier arrival counter
   int *d_err = nullptr;                 // deferred device-side error flag
+  float *d_head_o = nullptr;            // softmax head split over several tiles: the stage's outputs of this tick
+  unsigned int *d_head_ctr = nullptr;   // ... and the counter of tiles that have published theirs (monotonic)
+  unsigned int head_count = 0;          // value of that counter once everything enqueued so far has run
+  int head_parts = 0;                   // tiles of a softmax head that is split over several (0: none, or a single tile)
   unsigned long long bar_count = 0;     // arrivals enqueued so far
   long long spin_limit = 4000000;
   bool persistent = false;
@@ -1066,6 +1117,8 @@ void free_ctx(partime_ctx *c) {
   if (c->d_ms_tiles) (void)hipFree(c->d_ms_tiles);
   if (c->d_ms_head_ctr) (void)hipFree(c->d_ms_head_ctr);
   if (c->d_bar) (void)hipFree(c->d_bar);
+  if (c->d_head_o) (void)hipFree(c->d_head_o);
+  if (c->d_head_ctr) (void)hipFree(c->d_head_ctr);
   if (c->d_err) (void)hipFree(c->d_err);
   for (int p = 0; p < 2; ++p)
     if (c->d_hist[p]) (void)hipFree(c->d_hist[p]);
@@ -1145,14 +1198,10 @@ int build_plan(partime_ctx *c) {
         if (learn_phase_of(s, cmax) != ph) continue;
         const int unit = c->nw * s.rb;
         const bool head = i == NL - 1 && c->cfg.loss == PT_LOSS_CE;
-        int rows;
-        if (head) {
-          rows = s.out_dim;
-        } else {
-          long want = std::lround(per_tile / ((double)s.ld * c->esz) / unit) * unit;
-          rows = (int)std::min<long>(std::max<long>(want, unit), kMaxTileRows);
-          rows = std::min(rows, (s.out_dim + unit - 1) / unit * unit);
-        }
+        // (a row of the softmax head counts twice: its tiles read their rows once for the outputs, once to learn)
+        long want = std::lround(per_tile / ((double)s.ld * c->esz * (head ? 2 : 1)) / unit) * unit;
+        int rows = (int)std::min<long>(std::max<long>(want, unit), kMaxTileRows);
+        rows = std::min(rows, (s.out_dim + unit - 1) / unit * unit);
         s.rows_per_tile = rows;
         s.n_parts = (s.out_dim + rows - 1) / rows;
         n_tiles += s.n_parts;
@@ -1180,22 +1229,32 @@ int build_plan(partime_ctx *c) {
     };
     for (auto &s : c->stages)
       if (in_phase(s)) max_parts = std::max(max_parts, s.n_parts);
+    auto push = [&](int i, int p) {
+      const StageHost &s = c->stages[i];
+      TileDev t;
+      t.stage = i;
+      t.row0 = p * s.rows_per_tile;
+      t.nrows = std::min(s.rows_per_tile, s.out_dim - t.row0);
+      t.part = p;
+      c->tiles.push_back(t);
+    };
+    // The tiles of a softmax head wait for each other inside the launch: they come first, so that all of them are
+    // running before any tile that could keep a compute unit from them.
+    const int head_i = c->cfg.loss == PT_LOSS_CE && ph == cmax - 1 ? NL - 1 : -1;
+    if (head_i >= 0)
+      for (int p = 0; p < c->stages[head_i].n_parts; ++p) push(head_i, p);
     for (int p = 0; p < max_parts; ++p)
-      for (int i = 0; i < NL; ++i) {
-        StageHost &s = c->stages[i];
-        if (!in_phase(s) || p >= s.n_parts) continue;
-        TileDev t;
-        t.stage = i;
-        t.row0 = p * s.rows_per_tile;
-        t.nrows = std::min(s.rows_per_tile, s.out_dim - t.row0);
-        t.part = p;
-        c->tiles.push_back(t);
-      }
+      for (int i = 0; i < NL; ++i)
+        if (i != head_i && in_phase(c->stages[i]) && p < c->stages[i].n_parts) push(i, p);
     c->phase_cnt[ph] = (int)c->tiles.size() - c->phase_off[ph];
   }
   c->net.xs_len = xs_len;
   c->net.max_rows = max_rows;
-  c->net.red_len = std::max({(c->nw / 2) * xs_len, (max_rows + 63) / 64 * 64, c->nw * 64});
+  c->head_parts = c->cfg.loss == PT_LOSS_CE && c->stages[NL - 1].n_parts > 1 ? c->stages[NL - 1].n_parts : 0;
+  c->net.head_parts = c->head_parts;
+  // (a tile of the softmax head keeps all outputs of the stage where the error shares are reduced later)
+  c->net.red_len = std::max({(c->nw / 2) * xs_len, (max_rows + 63) / 64 * 64, c->nw * 64,
+                             c->cfg.loss == PT_LOSS_CE ? (c->stages[NL - 1].out_dim + 63) / 64 * 64 : 0});
   c->lds_bytes = ((size_t)xs_len + c->net.red_len + (size_t)max_rows * 5 + 2 * c->nw) * sizeof(float);
   if (c->lds_bytes > 160 * 1024) return fail(PT_EUNSUPPORTED, "tile needs %zu bytes of LDS", c->lds_bytes);
   return PT_OK;
@@ -2113,7 +2172,14 @@ int partime_init(const partime_config *cfg, const float *const *w_host, const fl
   INIT_TRY(hipMemset(c->d_bar, 0, sizeof(unsigned long long)));
   INIT_TRY(hipMalloc(&c->d_err, sizeof(int)));
   INIT_TRY(hipMemset(c->d_err, 0, sizeof(int)));
+  INIT_TRY(hipMalloc(&c->d_head_o, sizeof(float) * std::max(1, c->out_dim)));
+  INIT_TRY(hipMemset(c->d_head_o, 0, sizeof(float) * std::max(1, c->out_dim)));
+  INIT_TRY(hipMalloc(&c->d_head_ctr, sizeof(unsigned int)));
+  INIT_TRY(hipMemset(c->d_head_ctr, 0, sizeof(unsigned int)));
+  c->net.head_o = c->d_head_o; c->net.head_ctr = c->d_head_ctr; c->net.err = c->d_err; c->net.spin_limit = c->spin_limit;
   c->persistent = c->cfg.exec_mode == PT_EXEC_PERSISTENT;
+  // (a work-group of the persistent kernel that takes several tiles in turn could wait for a head tile of its own)
+  if (c->head_parts > 1 && c->tiles.size() > (size_t)c->max_grid) c->persistent = false;
   if (c->cmax > 1 || c->cfg.optimizer == PT_OPT_ADAM) c->persistent = false;   // no single-kernel form for these
   for (auto &l : c->layers)
     if (l.skip_from >= 0) c->persistent = false;
@@ -2306,6 +2372,9 @@ static int run_ticks(partime_ctx *c, const float *x_dev, const void *target_dev,
       pa.bar = c->d_bar;
       pa.err = c->d_err;
       pa.bar_base = c->bar_count;
+      pa.head_base = c->head_count;
+      pa.head_parts = learn ? (unsigned int)c->head_parts : 0u;
+      c->head_count += pa.head_parts * (unsigned int)n;
       pa.t0 = c->tick + base;
       pa.spin_limit = c->spin_limit;
       pa.n_ticks = n;
@@ -2333,6 +2402,8 @@ static int run_ticks(partime_ctx *c, const float *x_dev, const void *target_dev,
       a.cur = (int)(t & 1);
       a.rev = c->serpentine ? (int)(t & 1) : 0;
       a.tick = (int)(t % c->ring_period);
+      if (learn) c->head_count += (unsigned int)c->head_parts;
+      a.head_target = c->head_count;
       a.learn = learn && t >= c->fill && c->cfg.loss != PT_LOSS_NONE;
       a.tgt = nullptr;
       if (learn && c->cfg.loss != PT_LOSS_NONE)
@@ -2441,7 +2512,7 @@ static int sync_and_check(partime_ctx *ctx) {
   HIP_TRY(hipStreamSynchronize(ctx->stream));
   int flag = 0;
   HIP_TRY(hipMemcpy(&flag, ctx->d_err, sizeof(int), hipMemcpyDeviceToHost));
-  if (flag) return fail(PT_EHIP, "a bounded wait inside a kernel ran out (grid barrier of the persistent kernel, or the loss-head flag of the multi-stream backward launch); results after that tick are invalid");
+  if (flag) return fail(PT_EHIP, "a bounded wait inside a kernel ran out (grid barrier of the persistent kernel, the tiles of a softmax head waiting for each other, or the loss-head flag of the multi-stream matrix launch); results after that tick are invalid");
   return PT_OK;
 }
 
@@ -2693,6 +2764,10 @@ int partime_reset(partime_ctx *ctx) {
   if (!ctx) return fail(PT_EINVAL, "partime_reset: null context");
   HIP_TRY(hipStreamSynchronize(ctx->stream));
   if (ctx->d_ms_head_ctr) HIP_TRY(hipMemset(ctx->d_ms_head_ctr, 0, sizeof(unsigned int)));
+  if (ctx->d_head_ctr) {
+    HIP_TRY(hipMemset(ctx->d_head_ctr, 0, sizeof(unsigned int)));
+    ctx->head_count = 0;
+  }
   for (auto &v : ctx->cvs)
     for (int p = 0; p < 2; ++p) {
       if (v.act_buf[p]) HIP_TRY(hipMemset(v.act_buf[p], 0, (size_t)v.co_pad * v.H * v.W * 4));
