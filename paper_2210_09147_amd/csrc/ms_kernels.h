@@ -40,7 +40,7 @@ typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
 typedef float f32x4_t __attribute__((ext_vector_type(4)));
 
 constexpr int kMsS = 32;          // streams (fixed by the kernels' register layouts)
-constexpr int kMsTR = 512;        // rows per matrix tile
+constexpr int kMsTR = 512;        // rows per matrix tile, unless taller tiles make the launch one round of work-groups
 constexpr int kMsNWM = 4;         // waves of a matrix work-group: one per SIMD
 constexpr int kMsSB = 4;          // groups of 32 columns a wave takes: 128 columns, its share of E is 64 registers
 constexpr int kMsTC = 32 * kMsSB * kMsNWM;   // columns per matrix tile (stage sizes are padded to whole column tiles)
@@ -70,7 +70,7 @@ struct MsStage {
   const float *gin[2];       // error planes of the next stage [n_gparts][S][out_pad]
   int n_gparts;
   float *eout[2];            // this stage's error planes [n_rt][S][in_pad] (NULL for the first stage)
-  int n_rt;
+  int n_rt, tr;              // row tiles of the matrix launch (= error planes) and their height
 };
 
 // what one tick of one stage needs, with the ping-pong halves already chosen: plain scalars and pointers, so the
@@ -94,7 +94,7 @@ struct MsView {
   const float *gin_prev;
   int n_gparts;
   float *eout_cur;
-  int n_rt;
+  int n_rt, tr;
 };
 __device__ __forceinline__ MsView ms_view(const MsStage *sp, int cur, int fhalf) {
   MsView v;
@@ -113,7 +113,7 @@ __device__ __forceinline__ MsView ms_view(const MsStage *sp, int cur, int fhalf)
   v.gin_prev = cur ? sp->gin[0] : sp->gin[1];
   v.n_gparts = sp->n_gparts;
   v.eout_cur = cur ? sp->eout[1] : sp->eout[0];
-  v.n_rt = sp->n_rt;
+  v.n_rt = sp->n_rt; v.tr = sp->tr;
   return v;
 }
 
@@ -574,7 +574,7 @@ __device__ __forceinline__ void ms_delta_body(const MsNet &net, const MsTick &a,
 }
 
 // ------------------------------------------------------------------------------------------------
-// matrix kernel: tile = up to kMsTR rows x kMsTC columns of one stage; the four waves share the rows and take 128
+// matrix kernel: tile = a block of rows (the stage's tile height) x kMsTC columns of one stage; the four waves share the rows and take 128
 // columns each, so a wave keeps its share of E = W^T delta for its own columns to itself (64 VGPRs), while the four
 // shares of the coming tick's Z for a block of 32 rows meet in LDS (one work-group barrier per block).
 // MODE 0: a learning tick (E, update, forward of the coming tick); MODE 1: forward only.
@@ -594,7 +594,7 @@ template <int MODE, int OPT, bool HAS_E, bool FWD>
 __device__ __forceinline__ void ms_mat_tile(const MsNet &net, const MsTick &a, const MsTile &tl, const MsView &st,
                                             float (&zred)[2][kMsNWM][1024]) {
   const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6, li = lane & 15, g = lane >> 4;
-  const int row_lo = tl.a * kMsTR, row_hi = min(row_lo + kMsTR, st.out_pad);   // multiples of 32 (sizes are padded)
+  const int row_lo = tl.a * st.tr, row_hi = min(row_lo + st.tr, st.out_pad);   // multiples of 64 (sizes are padded)
   const int c0 = tl.b * kMsTC + 32 * kMsSB * wv;                                      // this wave's 128 columns
 
   // selectors that move a 16 x 32 register block into C layout (multiplication by a 0/1 matrix is exact)

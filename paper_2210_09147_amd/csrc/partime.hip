@@ -958,7 +958,7 @@ struct StageHost {
   float *err_buf[2] = {nullptr, nullptr};
   int n_parts = 0, rows_per_tile = 0;
   // multi-stream path: padded sizes and its extra buffers
-  int in_pad = 0, out_pad = 0, n_rt = 0;
+  int in_pad = 0, out_pad = 0, n_rt = 0, tr = 0;
   float *zbuf = nullptr;
   float *zp = nullptr;               // multi-stream path: partial pre-activation planes of the coming tick [n_ct][S][out_pad]
   int n_ct = 0;
@@ -1303,10 +1303,30 @@ int init_multistream(partime_ctx *c, const float *const *w_host, const float *co
     s.in_pad = pad512(l.in_dim);
     s.out_pad = pad512(l.out_dim);
     s.ld = s.in_pad;
-    s.n_rt = (s.out_pad + kMsTR - 1) / kMsTR;      // row tiles = error planes
     s.n_ct = s.in_pad / kMsTC;                     // column tiles = pre-activation planes
-    s.n_parts = s.n_rt;
     s.act_elems = (size_t)S * s.out_pad;
+  }
+  // Tile height of the matrix launch.  A work-group holds one wave per SIMD, so a launch of more tiles than compute units
+  // runs in rounds and the last one is rarely full: where taller tiles (fewer error planes as well) make the launch a
+  // single round they are taken.  The last stage keeps the short tiles: they start only once the loss head is done.
+  auto count_tiles = [&](int tr) {
+    int n = 1;
+    for (int h = 0; h < D; ++h) {
+      const StageHost &s = c->stages[h];
+      const int t = h == D - 1 ? std::min(tr, kMsTR) : tr;
+      n += (s.out_pad + t - 1) / t * s.n_ct;
+    }
+    return n;
+  };
+  int tr_all = kMsTR;
+  if (count_tiles(kMsTR) > c->n_cu)
+    for (int tr = 2 * kMsTR; tr <= 8 * kMsTR; tr *= 2)
+      if (count_tiles(tr) <= c->n_cu) { tr_all = tr; break; }
+  for (int h = 0; h < D; ++h) {
+    StageHost &s = c->stages[h];
+    s.tr = h == D - 1 ? std::min(tr_all, kMsTR) : tr_all;
+    s.n_rt = (s.out_pad + s.tr - 1) / s.tr;        // row tiles = error planes
+    s.n_parts = s.n_rt;
     s.err_elems = (size_t)s.n_rt * S * s.in_pad;
   }
   int rc;
@@ -1359,7 +1379,7 @@ int init_multistream(partime_ctx *c, const float *const *w_host, const float *co
       d.eout[p] = s.err_buf[p];
     }
     d.n_gparts = h < D - 1 ? c->stages[h + 1].n_rt : 0;
-    d.n_rt = s.n_rt;
+    d.n_rt = s.n_rt; d.tr = s.tr;
     for (int r = 0; r < s.out_pad; r += kMsVR) tv.push_back(MsTile{h, r, 0, 0});
     for (int r = 0; r < s.out_pad; r += kMsRowsF) ti.push_back(MsTile{h, r, kMsRowsF, 0});
     std::vector<MsTile> &dst = h == D - 1 ? tm_last : tm;
