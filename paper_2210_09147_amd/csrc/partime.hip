@@ -1132,6 +1132,15 @@ int upload_weights(partime_ctx *c, int h, const float *w_host, const float *b_ho
       HIP_TRY(hipMemcpy2D(s.W, (size_t)s.ld * 4, w_host, (size_t)s.in_dim * 4, (size_t)s.in_dim * 4, s.out_dim,
                           hipMemcpyHostToDevice));
     } else {
+      if (c->ms) {
+        // 32-stream path: the weights are kept in the order the matrix tiles request them
+        std::vector<unsigned short> tiled((size_t)s.out_pad * s.in_pad, 0);
+        for (int r = 0; r < s.out_dim; ++r)
+          for (int q = 0; q < s.in_dim; ++q) tiled[ms_woff(r, q, s.out_pad)] = host_bf16_rne(w_host[(size_t)r * s.in_dim + q]);
+        HIP_TRY(hipMemcpy(s.W, tiled.data(), tiled.size() * 2, hipMemcpyHostToDevice));
+        if (b_host) HIP_TRY(hipMemcpy(s.b, b_host, (size_t)s.out_dim * 4, hipMemcpyHostToDevice));
+        return PT_OK;
+      }
       std::vector<unsigned short> tmp((size_t)s.out_dim * s.ld, 0);
       for (int r = 0; r < s.out_dim; ++r)
         for (int q = 0; q < s.in_dim; ++q) tmp[(size_t)r * s.ld + q] = host_bf16_rne(w_host[(size_t)r * s.in_dim + q]);
@@ -2563,6 +2572,11 @@ int partime_get_state(partime_ctx *ctx, int layer, float *w_host, float *b_host)
     if (ctx->cfg.w_dtype == PT_F32) {
       HIP_TRY(hipMemcpy2D(w_host, (size_t)s.in_dim * 4, s.W, (size_t)s.ld * 4, (size_t)s.in_dim * 4, s.out_dim,
                           hipMemcpyDeviceToHost));
+    } else if (ctx->ms) {
+      std::vector<unsigned short> tiled((size_t)s.out_pad * s.in_pad);
+      HIP_TRY(hipMemcpy(tiled.data(), s.W, tiled.size() * 2, hipMemcpyDeviceToHost));
+      for (int r = 0; r < s.out_dim; ++r)
+        for (int q = 0; q < s.in_dim; ++q) w_host[(size_t)r * s.in_dim + q] = host_bf16_widen(tiled[ms_woff(r, q, s.out_pad)]);
     } else {
       std::vector<unsigned short> tmp((size_t)s.out_dim * s.ld);
       HIP_TRY(hipMemcpy(tmp.data(), s.W, tmp.size() * 2, hipMemcpyDeviceToHost));
@@ -2823,8 +2837,9 @@ int partime_reset(partime_ctx *ctx) {
   }
   for (auto &s : ctx->stages) {
     if (s.mW) {
-      HIP_TRY(hipMemset(s.mW, 0, (size_t)s.out_dim * s.ld * 4));
-      HIP_TRY(hipMemset(s.vW, 0, (size_t)s.out_dim * s.ld * 4));
+      const size_t nw = ctx->ms ? (size_t)s.out_pad * s.in_pad : (size_t)s.out_dim * s.ld;
+      HIP_TRY(hipMemset(s.mW, 0, nw * 4));
+      HIP_TRY(hipMemset(s.vW, 0, nw * 4));
       HIP_TRY(hipMemset(s.mb, 0, (size_t)s.out_dim * 4));
       HIP_TRY(hipMemset(s.vb, 0, (size_t)s.out_dim * 4));
     }
@@ -2880,10 +2895,18 @@ int partime_get_opt_state(partime_ctx *ctx, int layer, float *m_w_host, float *v
   StageHost &s = ctx->stages[layer];
   const float *src[2] = {s.mW, s.vW};
   float *dst[2] = {m_w_host, v_w_host};
-  for (int q = 0; q < 2; ++q)
-    if (dst[q])
-      HIP_TRY(hipMemcpy2D(dst[q], (size_t)s.in_dim * 4, src[q], (size_t)s.ld * 4, (size_t)s.in_dim * 4, s.out_dim,
-                          hipMemcpyDeviceToHost));
+  for (int q = 0; q < 2; ++q) {
+    if (!dst[q]) continue;
+    if (ctx->ms) {   // the moments are stored like the weights
+      std::vector<float> tiled((size_t)s.out_pad * s.in_pad);
+      HIP_TRY(hipMemcpy(tiled.data(), src[q], tiled.size() * 4, hipMemcpyDeviceToHost));
+      for (int r = 0; r < s.out_dim; ++r)
+        for (int k = 0; k < s.in_dim; ++k) dst[q][(size_t)r * s.in_dim + k] = tiled[ms_woff(r, k, s.out_pad)];
+      continue;
+    }
+    HIP_TRY(hipMemcpy2D(dst[q], (size_t)s.in_dim * 4, src[q], (size_t)s.ld * 4, (size_t)s.in_dim * 4, s.out_dim,
+                        hipMemcpyDeviceToHost));
+  }
   if (m_b_host) HIP_TRY(hipMemcpy(m_b_host, s.mb, (size_t)s.out_dim * 4, hipMemcpyDeviceToHost));
   if (v_b_host) HIP_TRY(hipMemcpy(v_b_host, s.vb, (size_t)s.out_dim * 4, hipMemcpyDeviceToHost));
   return PT_OK;
@@ -2906,10 +2929,18 @@ int partime_set_opt_state(partime_ctx *ctx, int layer, const float *m_w_host, co
   StageHost &s = ctx->stages[layer];
   float *dst[2] = {s.mW, s.vW};
   const float *src[2] = {m_w_host, v_w_host};
-  for (int q = 0; q < 2; ++q)
-    if (src[q])
-      HIP_TRY(hipMemcpy2D(dst[q], (size_t)s.ld * 4, src[q], (size_t)s.in_dim * 4, (size_t)s.in_dim * 4, s.out_dim,
-                          hipMemcpyHostToDevice));
+  for (int q = 0; q < 2; ++q) {
+    if (!src[q]) continue;
+    if (ctx->ms) {
+      std::vector<float> tiled((size_t)s.out_pad * s.in_pad, 0.f);
+      for (int r = 0; r < s.out_dim; ++r)
+        for (int k = 0; k < s.in_dim; ++k) tiled[ms_woff(r, k, s.out_pad)] = src[q][(size_t)r * s.in_dim + k];
+      HIP_TRY(hipMemcpy(dst[q], tiled.data(), tiled.size() * 4, hipMemcpyHostToDevice));
+      continue;
+    }
+    HIP_TRY(hipMemcpy2D(dst[q], (size_t)s.ld * 4, src[q], (size_t)s.in_dim * 4, (size_t)s.in_dim * 4, s.out_dim,
+                        hipMemcpyHostToDevice));
+  }
   if (m_b_host) HIP_TRY(hipMemcpy(s.mb, m_b_host, (size_t)s.out_dim * 4, hipMemcpyHostToDevice));
   if (v_b_host) HIP_TRY(hipMemcpy(s.vb, v_b_host, (size_t)s.out_dim * 4, hipMemcpyHostToDevice));
   return PT_OK;
