@@ -43,6 +43,7 @@ constexpr int kMsS = 32;          // streams (fixed by the kernels' register lay
 constexpr int kMsTR = 512;        // rows per matrix tile, unless taller tiles make the launch one round of work-groups
 constexpr int kMsNWM = 4;         // waves of a matrix work-group: one per SIMD
 constexpr int kMsSB = 4;          // groups of 32 columns a wave takes: 128 columns, its share of E is 64 registers
+constexpr int kMsRing = 2;        // register sets of a matrix tile: blocks of 32 rows in flight or being worked on (tile heights are multiples of 32 * kMsRing)
 constexpr int kMsTC = 32 * kMsSB * kMsNWM;   // columns per matrix tile (stage sizes are padded to whole column tiles)
 constexpr int kMsVR = 64;         // rows per tile of the vector kernel
 constexpr int kMsRW = 16;         // inference kernel: rows per wave
@@ -133,7 +134,7 @@ __device__ __forceinline__ MsView ms_view(const MsStage *sp, int cur, int fhalf)
 
 struct MsTile {
   int stage, a, b, kind;     // vector kernel: kind 0: rows [a, a + 64); kind 1: columns [a, a + 64) of the first stage's input.
-                             // matrix kernel: kind 0: a = row tile, b = column tile; kind 2: the loss head
+                             // matrix kernel: kind 0: a = row tile, b = column tile; kind 2: loss head, rows [a, a + 64)
 };
 
 struct MsNet {
@@ -142,7 +143,9 @@ struct MsNet {
   const MsTile *tiles_i;                       // inference launch (tile: a = first of 64 rows)
   int loss, out_dim, adam;
   float lr_over_s, inv_s, beta1, beta2, eps;
-  unsigned int *head_flag;  // sequence number of the last tick whose loss head is finished
+  unsigned int *head_flag;  // number of head tiles that have finished since the counter was last cleared
+  float *hstat;             // last stage: [tiles of 64 rows][S][2] softmax statistics left by the vector launch
+  float *hpart;             // last stage: the head tiles' shares of the squared error
   int *err;                 // raised when a bounded wait runs out
   long long spin_limit;
 };
@@ -155,7 +158,7 @@ struct MsTick {
   float *loss1;
   int cur, learn;
   int fhalf;            // which half of the published activations the forward product of this launch reads
-  unsigned int seq;     // tick + 1: what the loss head writes to head_flag when it is done
+  unsigned int seq;     // what head_flag reads once every head tile of this tick is done
   float adam_c1, adam_c2;   // lr / (1 - beta1^n), 1 / sqrt(1 - beta2^n)
 };
 
@@ -181,6 +184,28 @@ __device__ __forceinline__ float ms_step(const MsNet &net, const MsTick &a, floa
   m = fmaf(net.beta1, m, (1.f - net.beta1) * g);
   v = fmaf(net.beta2, v, (1.f - net.beta2) * g * g);
   return w - a.adam_c1 * m / (sqrtf(v) * a.adam_c2 + net.eps);
+}
+
+// acc[0..7] += the 8 consecutive floats at p0 + q * plane for q = 0 .. n - 1, added in ascending order.  The planes are
+// requested CH at a time, at clamped addresses: one request per trip of a loop with a run-time bound would be one memory
+// round trip after the other.
+template <int CH>
+__device__ __forceinline__ void ms_add_planes(const float *p0, int n, size_t plane, float (&acc)[8]) {
+  for (int q0 = 0; q0 < n; q0 += CH) {
+    float4 u[CH][2];
+#pragma unroll
+    for (int i = 0; i < CH; ++i) {
+      const float *p = p0 + (size_t)min(q0 + i, n - 1) * plane;
+      u[i][0] = ldg_f4(p);
+      u[i][1] = ldg_f4(p + 4);
+    }
+#pragma unroll
+    for (int i = 0; i < CH; ++i) {
+      const bool on = q0 + i < n;
+      acc[0] += on ? u[i][0].x : 0.f; acc[1] += on ? u[i][0].y : 0.f; acc[2] += on ? u[i][0].z : 0.f; acc[3] += on ? u[i][0].w : 0.f;
+      acc[4] += on ? u[i][1].x : 0.f; acc[5] += on ? u[i][1].y : 0.f; acc[6] += on ? u[i][1].z : 0.f; acc[7] += on ? u[i][1].w : 0.f;
+    }
+  }
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -232,14 +257,8 @@ __global__ __launch_bounds__(256) void ms_vec_kernel(MsNet net, MsTick a) {
   const int r = tl.a + 8 * rq;
   const float4 b0 = ldg_f4(st.b + r), b1 = ldg_f4(st.b + r + 4);
   float z[8] = {b0.x, b0.y, b0.z, b0.w, b1.x, b1.y, b1.z, b1.w};
-  {
-    const size_t plane = (size_t)kMsS * st.out_pad;
-    const float *zp = st.zp + (size_t)s * st.out_pad + r;
-    for (int q = 0; q < st.n_ct; ++q) {
-      const float4 u0 = ldg_f4(zp + q * plane), u1 = ldg_f4(zp + q * plane + 4);
-      z[0] += u0.x; z[1] += u0.y; z[2] += u0.z; z[3] += u0.w; z[4] += u1.x; z[5] += u1.y; z[6] += u1.z; z[7] += u1.w;
-    }
-  }
+  const size_t plane = (size_t)kMsS * st.out_pad;
+  ms_add_planes<8>(st.zp + (size_t)s * st.out_pad + r, st.n_ct, plane, z);
   float o[8];
 #pragma unroll
   for (int j = 0; j < 8; ++j) o[j] = act_fwd(st.act, z[j]);
@@ -247,9 +266,30 @@ __global__ __launch_bounds__(256) void ms_vec_kernel(MsNet net, MsTick a) {
 #pragma unroll
     for (int j = 0; j < 8; ++j)
       if (r + j < st.out_dim) stg_f(a.out + (size_t)s * st.out_dim + r + j, o[j]);
-    if (LEARN) {   // the loss head (first work-group of the matrix launch) needs every pre-activation of the stage
+    if (LEARN) {   // the loss head (first work-groups of the matrix launch) reads the pre-activations of the stage
       stg_f4(st.zbuf + (size_t)s * st.out_pad + r, make_float4(z[0], z[1], z[2], z[3]));
       stg_f4(st.zbuf + (size_t)s * st.out_pad + r + 4, make_float4(z[4], z[5], z[6], z[7]));
+      if (net.loss == PT_LOSS_CE) {
+        // this tile's share of the softmax statistics of stream s: its largest output and the sum of exp(output - largest)
+        // over its rows (rows beyond out_dim are not outputs); the 8 lanes of a stream are neighbours
+        float m = -INFINITY;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) m = r + j < st.out_dim ? fmaxf(m, o[j]) : m;
+        m = fmaxf(m, __shfl_xor(m, 1, 64));
+        m = fmaxf(m, __shfl_xor(m, 2, 64));
+        m = fmaxf(m, __shfl_xor(m, 4, 64));
+        float t = 0.f;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) t += r + j < st.out_dim ? expf(o[j] - m) : 0.f;
+        t += __shfl_xor(t, 1, 64);
+        t += __shfl_xor(t, 2, 64);
+        t += __shfl_xor(t, 4, 64);
+        if (rq == 0) {
+          float *hp = net.hstat + ((size_t)(tl.a / kMsVR) * kMsS + s) * 2;
+          stg_f(hp, m);
+          stg_f(hp + 1, t);
+        }
+      }
     }
     return;
   }
@@ -262,13 +302,8 @@ __global__ __launch_bounds__(256) void ms_vec_kernel(MsNet net, MsTick a) {
   if (LEARN) {
     // a3, a4: g = the error the next stage published one tick earlier (sum of its row-tile planes, Eq. 11),
     // delta = rnd(g * phi'(z)) with this tick's z (Eq. 9).  Padding rows have z = 0 and g = 0, hence delta = 0.
-    const size_t plane = (size_t)kMsS * st.out_pad;
-    const float *gp = st.gin_prev + (size_t)s * st.out_pad + r;
     float g[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-    for (int q = 0; q < st.n_gparts; ++q) {
-      const float4 u0 = ldg_f4(gp + q * plane), u1 = ldg_f4(gp + q * plane + 4);
-      g[0] += u0.x; g[1] += u0.y; g[2] += u0.z; g[3] += u0.w; g[4] += u1.x; g[5] += u1.y; g[6] += u1.z; g[7] += u1.w;
-    }
+    ms_add_planes<4>(st.gin_prev + (size_t)s * st.out_pad + r, st.n_gparts, plane, g);
 #pragma unroll
     for (int j = 0; j < 4; ++j) pd[j] = pack_bf16(g[2 * j] * act_der(st.act, z[2 * j]), g[2 * j + 1] * act_der(st.act, z[2 * j + 1]));
     stg16(st.dlt + (size_t)s * st.out_pad + r, make_uint4(pd[0], pd[1], pd[2], pd[3]));
@@ -476,116 +511,108 @@ __global__ __launch_bounds__(256) void ms_infer_kernel(MsNet net, MsTick a) {
 }
 
 // ------------------------------------------------------------------------------------------------
-// loss head of the last stage (a2, a4 and the bias part of a6), rows [tl.a, tl.a + tl.b): thread per row, loop over
-// the streams.  Run by one work-group over the whole stage.
-// ------------------------------------------------------------------------------------------------
+// loss head of the last stage (a2, a4 and the bias part of a6): a tile is 64 rows x the 32 streams, thread (stream s,
+// group of 8 rows) as in the vector kernel.  A softmax needs every output of its stream: the vector launch has left,
+// per tile of 64 rows and per stream, the largest output and the sum of exp(output - largest); every head tile combines
+// them in the same order, so all tiles work with the same statistics.  The head tiles are the first work-groups of the
+// matrix launch; each counts itself in when its deltas are in memory, and the matrix tiles of the last stage start when
+// all have done so.  (One work-group for the whole head took 25 us, with the last stage's tiles waiting behind it.)
 // The activation is a template parameter: with a run-time switch inside the element loops every load sits in its
 // own basic block and is waited for before the next one is issued.
-template <int ACT, int NT>
-__device__ __forceinline__ void ms_delta_body(const MsNet &net, const MsTick &a, const MsTile &tl, const MsView &st,
-                                              float *smax, float *ssum, float *sloss, float *sred) {
-  const int tid = threadIdx.x;
-  const bool ce = st.is_last && net.loss == PT_LOSS_CE, mse = st.is_last && net.loss == PT_LOSS_MSE;
+// ------------------------------------------------------------------------------------------------
+template <int ACT>
+__device__ __forceinline__ void ms_head_tile(const MsNet &net, const MsTick &a, const MsTile &tl, const MsView &st, float *lds) {
+  unsigned short *tr = reinterpret_cast<unsigned short *>(lds);   // bf16 [64 rows][32 streams]
+  float *sloss = lds + kMsVR * kMsS / 2, *sred = sloss + kMsS;
+  const int tid = threadIdx.x, s = tid >> 3, rq = tid & 7, trow = tid >> 2, tq = tid & 3;
+  const bool ce = net.loss == PT_LOSS_CE, mse = net.loss == PT_LOSS_MSE;
   const float inv_n = 1.f / (float)net.out_dim;
+  const int r = tl.a + 8 * rq;
+  const float4 z0 = ldg_f4(st.zbuf + (size_t)s * st.out_pad + r), z1 = ldg_f4(st.zbuf + (size_t)s * st.out_pad + r + 4);
+  const float z[8] = {z0.x, z0.y, z0.z, z0.w, z1.x, z1.y, z1.z, z1.w};
+  float gg[8], sq = 0.f, smax = 0.f, ssum = 1.f;
+  int ys = 0;
   if (ce) {
-    // softmax statistics per stream over the whole stage (this tile covers it): 8 lanes share a stream
-    if (tid < 8 * kMsS) {
-      const int s = tid >> 3, part = tid & 7;
-      const float *z = st.zbuf + (size_t)s * st.out_pad;
-      float m = -INFINITY;
-#pragma unroll 16
-      for (int r = part; r < st.out_dim; r += 8) m = fmaxf(m, act_fwd(ACT, ldg_f(z + r)));
-      m = fmaxf(m, __shfl_xor(m, 1, 64));
-      m = fmaxf(m, __shfl_xor(m, 2, 64));
-      m = fmaxf(m, __shfl_xor(m, 4, 64));
-      float t = 0.f;
-#pragma unroll 16
-      for (int r = part; r < st.out_dim; r += 8) t += expf(act_fwd(ACT, ldg_f(z + r)) - m);
-      t += __shfl_xor(t, 1, 64);
-      t += __shfl_xor(t, 2, 64);
-      t += __shfl_xor(t, 4, 64);
-      if (part == 0) {
-        smax[s] = m;
-        ssum[s] = t;
-      }
+    const int n_vt = st.out_pad / kMsVR;
+    const float *hp = net.hstat + 2 * s;
+    smax = -INFINITY;
+    for (int t = 0; t < n_vt; ++t) smax = fmaxf(smax, ldg_f(hp + (size_t)t * 2 * kMsS));
+    ssum = 0.f;
+    for (int t = 0; t < n_vt; ++t) {
+      const float mt = ldg_f(hp + (size_t)t * 2 * kMsS), et = ldg_f(hp + (size_t)t * 2 * kMsS + 1);
+      ssum += et > 0.f ? et * expf(mt - smax) : 0.f;   // (a tile of padding rows only has no outputs)
     }
-    __syncthreads();
-    if (tl.a == 0 && tid < kMsS) {
-      const int ys = min(max(ldg_i(static_cast<const int *>(a.tgt) + tid), 0), st.out_dim - 1);
-      const float oy = act_fwd(ACT, ldg_f(st.zbuf + (size_t)tid * st.out_pad + ys));
-      sloss[tid] = -(oy - smax[tid] - logf(ssum[tid]));
+    ys = min(max(ldg_i(static_cast<const int *>(a.tgt) + s), 0), st.out_dim - 1);
+    const float inv = 1.f / ssum;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) gg[j] = a.learn ? expf(act_fwd(ACT, z[j]) - smax) * inv - (r + j == ys ? 1.f : 0.f) : 0.f;
+  } else if (mse) {
+    float y[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) y[j] = ldg_f(static_cast<const float *>(a.tgt) + (size_t)s * st.out_dim + min(r + j, st.out_dim - 1));
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      const float df = act_fwd(ACT, z[j]) - y[j];
+      if (r + j < st.out_dim) sq = fmaf(df, df, sq);
+      gg[j] = a.learn ? 2.f * df * inv_n : 0.f;
     }
-    __syncthreads();
-    if (tl.a == 0 && tid == 0) {
-      float L = 0.f;
-      for (int s = 0; s < kMsS; ++s) L += sloss[s];
-      a.loss1[0] = a.learn ? L * net.inv_s : 0.f;
-    }
+  } else {
+#pragma unroll
+    for (int j = 0; j < 8; ++j) gg[j] = 0.f;
   }
-  float sq = 0.f;
-  for (int r = tl.a + tid; r < tl.a + tl.b; r += NT) {
-    float dsum = 0.f;
-    bf16_t *dstT = st.dltT + (size_t)r * kMsS;
-    const bool valid = r < st.out_dim;
-    const int rc = min(r, st.out_dim - 1);              // loads are unconditional; padding rows are zeroed below
-    for (int sg = 0; sg < kMsS / 8; ++sg) {
-      float d[8], z[8], gg[8];
+  // a4 for the last stage; the rounded delta is what every product (and the bias update) sees.  Rows beyond out_dim are
+  // padding: their delta is zero
+  unsigned int pd[4];
 #pragma unroll
-      for (int j = 0; j < 8; ++j) z[j] = ldg_f(st.zbuf + (size_t)(8 * sg + j) * st.out_pad + rc);
-      if (ce) {
-        int ys[8];
+  for (int j = 0; j < 4; ++j)
+    pd[j] = pack_bf16(r + 2 * j < st.out_dim ? gg[2 * j] * act_der(ACT, z[2 * j]) : 0.f,
+                      r + 2 * j + 1 < st.out_dim ? gg[2 * j + 1] * act_der(ACT, z[2 * j + 1]) : 0.f);
+  stg16(st.dlt + (size_t)s * st.out_pad + r, make_uint4(pd[0], pd[1], pd[2], pd[3]));
 #pragma unroll
-        for (int j = 0; j < 8; ++j) ys[j] = ldg_i(static_cast<const int *>(a.tgt) + 8 * sg + j);
-#pragma unroll
-        for (int j = 0; j < 8; ++j) {
-          const int s = 8 * sg + j;
-          const int yc = min(max(ys[j], 0), st.out_dim - 1);
-          gg[j] = a.learn ? expf(act_fwd(ACT, z[j]) - smax[s]) / ssum[s] - (rc == yc ? 1.f : 0.f) : 0.f;
-        }
-      } else if (mse) {
-        float y[8];
-#pragma unroll
-        for (int j = 0; j < 8; ++j) y[j] = ldg_f(static_cast<const float *>(a.tgt) + (size_t)(8 * sg + j) * st.out_dim + rc);
-#pragma unroll
-        for (int j = 0; j < 8; ++j) {
-          const float df = act_fwd(ACT, z[j]) - y[j];
-          if (valid) sq = fmaf(df, df, sq);
-          gg[j] = a.learn ? 2.f * df * inv_n : 0.f;
-        }
-      } else {
-#pragma unroll
-        for (int j = 0; j < 8; ++j) gg[j] = 0.f;
-      }
-      __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-      for (int j = 0; j < 8; ++j) d[j] = valid ? gg[j] * act_der(ACT, z[j]) : 0.f;
-      // the rounded delta is what every product (and the bias update) sees
-      unsigned int p[4];
-#pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        p[j] = pack_bf16(d[2 * j], d[2 * j + 1]);
-        dsum += bf16_lo(p[j]) + bf16_hi(p[j]);
-        stg_u16(st.dlt + (size_t)(8 * sg + 2 * j) * st.out_pad + r, p[j] & 0xffffu);
-        stg_u16(st.dlt + (size_t)(8 * sg + 2 * j + 1) * st.out_pad + r, p[j] >> 16);
-      }
-      stg16(dstT + 8 * sg, make_uint4(p[0], p[1], p[2], p[3]));
-    }
-    if (r < st.out_dim) {
-      float mq = net.adam ? ldg_f(st.mb + r) : 0.f, vq = net.adam ? ldg_f(st.vb + r) : 0.f;
-      stg_f(st.b + r, ms_step(net, a, ldg_f(st.b + r), dsum, mq, vq));
-      if (net.adam) {
-        stg_f(st.mb + r, mq);
-        stg_f(st.vb + r, vq);
-      }
-    }
+  for (int j = 0; j < 4; ++j) {
+    tr[(8 * rq + 2 * j) * kMsS + s] = (unsigned short)(pd[j] & 0xffffu);
+    tr[(8 * rq + 2 * j + 1) * kMsS + s] = (unsigned short)(pd[j] >> 16);
   }
+  if (ce && tl.a == 0 && rq == 0)
+    sloss[s] = -(act_fwd(ACT, ldg_f(st.zbuf + (size_t)s * st.out_pad + ys)) - smax - logf(ssum));
   if (mse) {
     sq = wave_sum(sq);
     if ((tid & 63) == 0) sred[tid >> 6] = sq;
-    __syncthreads();
-    if (tid == 0) {
+  }
+  __syncthreads();
+  const int row = tl.a + trow;
+  const uint4 d = *reinterpret_cast<const uint4 *>(&tr[trow * kMsS + 8 * tq]);
+  stg16(st.dltT + (size_t)row * kMsS + 8 * tq, d);
+  float dsum = bf16_lo(d.x) + bf16_hi(d.x) + bf16_lo(d.y) + bf16_hi(d.y) + bf16_lo(d.z) + bf16_hi(d.z) + bf16_lo(d.w) + bf16_hi(d.w);
+  dsum += __shfl_xor(dsum, 1, 64);
+  dsum += __shfl_xor(dsum, 2, 64);
+  if (tq == 0 && row < st.out_dim) {
+    float mq = net.adam ? ldg_f(st.mb + row) : 0.f, vq = net.adam ? ldg_f(st.vb + row) : 0.f;
+    stg_f(st.b + row, ms_step(net, a, ldg_f(st.b + row), dsum, mq, vq));
+    if (net.adam) {
+      stg_f(st.mb + row, mq);
+      stg_f(st.vb + row, vq);
+    }
+  }
+  if (ce && tl.a == 0 && tid == 0) {
+    float L = 0.f;
+    for (int q = 0; q < kMsS; ++q) L += sloss[q];
+    a.loss1[0] = a.learn ? L * net.inv_s : 0.f;
+  }
+  if (mse && tid == 0) {
+    float t = 0.f;
+    for (int w = 0; w < kMsNWM; ++w) t += sred[w];
+    __hip_atomic_store(net.hpart + tl.a / kMsVR, t, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  }
+  // everything above is released to the rest of the device before this tile counts itself in
+  __threadfence();
+  __syncthreads();
+  if (tid == 0) {
+    const unsigned int before = __hip_atomic_fetch_add(net.head_flag, 1u, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
+    if (mse && before + 1u == a.seq) {
+      // the last head tile of the tick adds the tiles' shares of the squared error in a fixed order
       float t = 0.f;
-      for (int w = 0; w < NT / 64; ++w) t += sred[w];
+      for (int q = 0; q < st.out_pad / kMsVR; ++q) t += __hip_atomic_load(net.hpart + q, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
       a.loss1[0] = a.learn ? t * inv_n * net.inv_s : 0.f;
     }
   }
@@ -672,7 +699,76 @@ __device__ __forceinline__ void ms_mat_tile(const MsNet &net, const MsTick &a, c
     for (int b = 0; b < 2; ++b)
 #pragma unroll
       for (int h = 0; h < 2; ++h) facc[b][h] = f32x4_t{0.f, 0.f, 0.f, 0.f};
-    if (MODE == 0) {
+    if (MODE == 0 && OPT == 0) {
+      // Plain SGD.  A wave is alone on its SIMD, so whatever waits for a result of the matrix pipe waits in full: the
+      // products whose results the vector pipe works on are issued a whole phase ahead of that work, and each phase
+      // pairs products with vector work that does not depend on them.
+      const f32x4_t z4 = {0.f, 0.f, 0.f, 0.f};
+      f32x4_t t[kMsSB][2][2], u[kMsSB][2][2];
+      // phase 1: the block turned into the other operand layout, W[r0 + 16 q + 4 g + j][c0 + 32 sb + 16 c + li] in t[sb][c][q]
+      if (HAS_E) {
+#pragma unroll
+        for (int sb = 0; sb < kMsSB; ++sb)
+#pragma unroll
+          for (int c = 0; c < 2; ++c)
+#pragma unroll
+            for (int q = 0; q < 2; ++q) t[sb][c][q] = mfma16(k.w[sb][q], isel[c], z4);
+      }
+      __builtin_amdgcn_sched_barrier(0);
+      // phase 2: the update products delta rnd(X)^T (they come out as lane (row li, k = 8 g + 4 e + j), the layout of the
+      // loaded weights), while the vector pipe rounds the turned block
+      uint4 wt[kMsSB][2];
+#pragma unroll
+      for (int sb = 0; sb < kMsSB; ++sb)
+#pragma unroll
+        for (int b = 0; b < 2; ++b) {
+#pragma unroll
+          for (int e = 0; e < 2; ++e) u[sb][b][e] = mfma16(xop[sb][e], k.du[b], z4);
+          if (HAS_E)
+            wt[sb][b] = make_uint4(pack_bf16(t[sb][b][0][0], t[sb][b][0][1]), pack_bf16(t[sb][b][0][2], t[sb][b][0][3]),
+                                   pack_bf16(t[sb][b][1][0], t[sb][b][1][1]), pack_bf16(t[sb][b][1][2], t[sb][b][1][3]));
+        }
+      if (HAS_E) {
+#pragma unroll
+        for (int i = 0; i < 4 * kMsSB; ++i) {
+          __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // one product,
+          __builtin_amdgcn_sched_group_barrier(0x002, 6, 0);   // then vector work under it
+        }
+      }
+      __builtin_amdgcn_sched_barrier(0);
+      // phase 3: a6, W <- rnd(W - eta/S * delta rnd(X)^T), on the vector pipe; under it a5, E[k][s] += sum_r W[r][k]
+      // delta[r][s] with the rows as loaded, and a1 of the coming tick (first half of Eq. 6) with the rows as stored
+#pragma unroll
+      for (int sb = 0; sb < kMsSB; ++sb)
+#pragma unroll
+        for (int b = 0; b < 2; ++b) {
+          const uint4 w = k.w[sb][b];
+          const f32x4_t u0 = u[sb][b][0], u1 = u[sb][b][1];
+          uint4 o;
+          o.x = pack_bf16(bf16_lo(w.x) - scale * u0[0], bf16_hi(w.x) - scale * u0[1]);
+          o.y = pack_bf16(bf16_lo(w.y) - scale * u0[2], bf16_hi(w.y) - scale * u0[3]);
+          o.z = pack_bf16(bf16_lo(w.z) - scale * u1[0], bf16_hi(w.z) - scale * u1[1]);
+          o.w = pack_bf16(bf16_lo(w.w) - scale * u1[2], bf16_hi(w.w) - scale * u1[3]);
+          stg16(st.W + wbase + (size_t)(r0 >> 5) * kMsBlk + (2 * sb + b) * 512, o);
+          if (HAS_E) {
+#pragma unroll
+            for (int h = 0; h < 2; ++h) eacc[sb][b][h] = mfma16(wt[sb][b], k.de[h], eacc[sb][b][h]);
+          }
+          if (FWD) {
+#pragma unroll
+            for (int h = 0; h < 2; ++h) facc[b][h] = mfma16(o, xf[sb][h], facc[b][h]);
+          }
+        }
+      {
+        constexpr int n_mfma = 2 * kMsSB * ((HAS_E ? 2 : 0) + (FWD ? 2 : 0));
+#pragma unroll
+        for (int i = 0; i < n_mfma; ++i) {
+          __builtin_amdgcn_sched_group_barrier(0x002, (HAS_E && FWD) ? 7 : 14, 0);
+          __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        }
+      }
+      __builtin_amdgcn_sched_barrier(0);
+    } else if (MODE == 0) {
       // Adam: the moments of 32 columns (both 16-row halves) travel one column group ahead of the arithmetic
       float4 mv[OPT == 1 ? 2 : 1][2][4];
       auto load_mv = [&](int buf, int sb) {
@@ -766,28 +862,30 @@ __device__ __forceinline__ void ms_mat_tile(const MsNet &net, const MsTick &a, c
     }
   };
   {
-    // Two register sets: the next block of 32 rows is requested before the current one is worked on.  The loop has no
-    // data-dependent branch (a tile is a whole number of 64-row pairs; the request after the last block is clamped
-    // onto the last block and never used): where paths with different numbers of requests in flight meet, the
-    // compiler has to wait for all of them, and the prefetch would no longer run ahead of the arithmetic.
-    MsBlock ka, kb;
+    // A ring of kMsRing register sets: block i + kMsRing - 1 is requested before block i is worked on.  A wave is alone on
+    // its SIMD, so nothing else covers the time its requests are under way.  The loop has no data-dependent branch (a
+    // tile is a whole number of rings; requests beyond the last block are clamped onto it and never used): where paths
+    // with different numbers of requests in flight meet, the compiler has to wait for all of them, and the prefetch
+    // would no longer run ahead of the arithmetic.
+    constexpr int NR = (MODE == 0 && OPT == 1) ? 2 : kMsRing;   // (with Adam the moments take the registers)
+    MsBlock kq[NR];
     // Odd ticks walk the tile's rows from the bottom up: what a tick wrote last is what the next tick reads first, while
     // it is still in the memory-side cache.
     const int n_blk = (row_hi - row_lo) >> 5;
     const bool rev = (a.cur & 1) != 0;
     auto row_of = [&](int i) { return rev ? row_hi - 32 - 32 * i : row_lo + 32 * i; };
-    load_block(ka, row_of(0));
-    for (int i = 0; i < n_blk; i += 2) {
-      // (the scheduling barriers keep the requests where they are written: left alone, the scheduler sinks every
-      // load next to its first use, i.e. behind the arithmetic it is meant to overlap)
-      load_block(kb, row_of(i + 1));
-      __builtin_amdgcn_sched_barrier(0);
-      process_block(ka, row_of(i), 0);
-      __builtin_amdgcn_sched_barrier(0);
-      load_block(ka, row_of(min(i + 2, n_blk - 1)));
-      __builtin_amdgcn_sched_barrier(0);
-      process_block(kb, row_of(i + 1), 1);
-      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int u = 0; u < NR - 1; ++u) load_block(kq[u], row_of(u));
+    for (int i = 0; i < n_blk; i += NR) {
+#pragma unroll
+      for (int u = 0; u < NR; ++u) {
+        // (the scheduling barriers keep the requests where they are written: left alone, the scheduler sinks every
+        // load next to its first use, i.e. behind the arithmetic it is meant to overlap)
+        load_block(kq[(u + NR - 1) % NR], row_of(min(i + u + NR - 1, n_blk - 1)));
+        __builtin_amdgcn_sched_barrier(0);
+        process_block(kq[u], row_of(i + u), u & 1);
+        __builtin_amdgcn_sched_barrier(0);
+      }
     }
   }
 
@@ -812,29 +910,24 @@ __global__ __launch_bounds__(64 * kMsNWM) void ms_mat_kernel(MsNet net, MsTick a
   const MsView st = ms_view(net.stages + tl.stage, a.cur, a.fhalf);
   const int tid = threadIdx.x;
   if (MODE == 0 && tl.kind == 2) {
-    // a2 for the last stage: needs every output of the stage, so one work-group does it, the first of the launch.
-    // Its results are released to the rest of the device before the flag is raised.
+    // a2 for the last stage: 64 of its rows
     float *hs = &zred[0][0][0];
-    const MsTile whole{tl.stage, 0, st.out_pad, 0};
     switch (st.act) {
-      case PT_RELU: ms_delta_body<PT_RELU, 64 * kMsNWM>(net, a, whole, st, hs, hs + kMsS, hs + 2 * kMsS, hs + 3 * kMsS); break;
-      case PT_GELU: ms_delta_body<PT_GELU, 64 * kMsNWM>(net, a, whole, st, hs, hs + kMsS, hs + 2 * kMsS, hs + 3 * kMsS); break;
-      default: ms_delta_body<PT_ID, 64 * kMsNWM>(net, a, whole, st, hs, hs + kMsS, hs + 2 * kMsS, hs + 3 * kMsS); break;
+      case PT_RELU: ms_head_tile<PT_RELU>(net, a, tl, st, hs); break;
+      case PT_GELU: ms_head_tile<PT_GELU>(net, a, tl, st, hs); break;
+      default: ms_head_tile<PT_ID>(net, a, tl, st, hs); break;
     }
-    __threadfence();
-    __syncthreads();
-    if (tid == 0) __hip_atomic_store(net.head_flag, a.seq, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
     return;
   }
   if (MODE == 0 && st.is_last) {
-    // delta of the last stage comes from the work-group above.  It has the lowest index of the launch, so it is
+    // delta of the last stage comes from the head tiles above.  They have the lowest indices of the launch, so they are
     // running or done by the time this one starts; the wait is bounded all the same, and when it runs out the
     // error flag is raised and the tile leaves the weights alone.
     __shared__ int s_ok;
     if (tid == 0) {
       long long spins = 0;
       int ok = 1;
-      while (__hip_atomic_load(net.head_flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != a.seq) {
+      while ((int)(__hip_atomic_load(net.head_flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) - a.seq) < 0) {
         __builtin_amdgcn_s_sleep(1);
         if (++spins > net.spin_limit) {
           __hip_atomic_store(net.err, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);

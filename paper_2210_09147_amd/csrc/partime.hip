@@ -153,6 +153,10 @@ __device__ __forceinline__ uint2 ldg8(const void *p) { const pt_v2u t = *(const 
 __device__ __forceinline__ void stg8(void *p, const uint2 &v) { const pt_v2u t = {v.x, v.y}; *(g_v2u *)p = t; }
 __device__ __forceinline__ float4 ldg_f4(const void *p) { const pt_v4f t = *(const g_v4f *)p; return make_float4(t.x, t.y, t.z, t.w); }
 __device__ __forceinline__ void stg_f4(void *p, const float4 &v) { const pt_v4f t = {v.x, v.y, v.z, v.w}; *(g_v4f *)p = t; }
+// streaming variants: what is written once and read once a whole launch later (partial-sum planes) is kept out of the
+// memory-side cache, which is better spent on the weights
+__device__ __forceinline__ float4 ldg_f4_stream(const void *p) { const pt_v4f t = __builtin_nontemporal_load((const g_v4f *)p); return make_float4(t.x, t.y, t.z, t.w); }
+__device__ __forceinline__ void stg_f4_stream(void *p, const float4 &v) { const pt_v4f t = {v.x, v.y, v.z, v.w}; __builtin_nontemporal_store(t, (g_v4f *)p); }
 __device__ __forceinline__ float ldg_f(const void *p) { return *(const g_f32 *)p; }
 __device__ __forceinline__ void stg_f(void *p, float v) { *(g_f32 *)p = v; }
 __device__ __forceinline__ int ldg_i(const void *p) { return *(const g_i32 *)p; }
@@ -1034,6 +1038,9 @@ struct partime_ctx {
   MsStage *d_ms_stages = nullptr;
   MsTile *d_ms_tiles = nullptr;
   unsigned int *d_ms_head_ctr = nullptr;
+  unsigned int ms_head_count = 0;       // what the counter reads once every head tile launched so far is done
+  int ms_n_head = 0;                    // head tiles per learning tick
+  float *d_ms_hstat = nullptr, *d_ms_hpart = nullptr;
   int n_tiles_v = 0, n_prep = 0;        // vector launch; its first n_prep tiles round the first stage's input
   int n_tiles_m = 0;                    // matrix launch of a learning tick (loss head first, last stage's tiles last)
   int n_tiles_f = 0, n_tiles_f0 = 0;    // forward-only matrix launch, stage by stage; the first n_tiles_f0 are the first stage's
@@ -1116,6 +1123,8 @@ void free_ctx(partime_ctx *c) {
   if (c->d_ms_stages) (void)hipFree(c->d_ms_stages);
   if (c->d_ms_tiles) (void)hipFree(c->d_ms_tiles);
   if (c->d_ms_head_ctr) (void)hipFree(c->d_ms_head_ctr);
+  if (c->d_ms_hstat) (void)hipFree(c->d_ms_hstat);
+  if (c->d_ms_hpart) (void)hipFree(c->d_ms_hpart);
   if (c->d_bar) (void)hipFree(c->d_bar);
   if (c->d_head_o) (void)hipFree(c->d_head_o);
   if (c->d_head_ctr) (void)hipFree(c->d_head_ctr);
@@ -1319,7 +1328,7 @@ int init_multistream(partime_ctx *c, const float *const *w_host, const float *co
   // runs in rounds and the last one is rarely full: where taller tiles (fewer error planes as well) make the launch a
   // single round they are taken.  The last stage keeps the short tiles: they start only once the loss head is done.
   auto count_tiles = [&](int tr) {
-    int n = 1;
+    int n = 0;   // (the head tiles are not counted: they are gone within a few microseconds)
     for (int h = 0; h < D; ++h) {
       const StageHost &s = c->stages[h];
       const int t = h == D - 1 ? std::min(tr, kMsTR) : tr;
@@ -1401,7 +1410,12 @@ int init_multistream(partime_ctx *c, const float *const *w_host, const float *co
   }
   // matrix launch of a learning tick: the loss head of the last stage first, the last stage's own tiles (which wait
   // for the delta it provides) last
-  tm.insert(tm.begin(), MsTile{D - 1, 0, 0, 2});
+  {
+    std::vector<MsTile> heads;
+    for (int r = 0; r < c->stages[D - 1].out_pad; r += kMsVR) heads.push_back(MsTile{D - 1, r, kMsVR, 2});
+    c->ms_n_head = (int)heads.size();
+    tm.insert(tm.begin(), heads.begin(), heads.end());
+  }
   tm.insert(tm.end(), tm_last.begin(), tm_last.end());
   c->n_tiles_v = (int)tv.size();
   c->n_tiles_m = (int)tm.size();
@@ -1429,6 +1443,11 @@ int init_multistream(partime_ctx *c, const float *const *w_host, const float *co
   MS_TRY(hipMalloc(reinterpret_cast<void **>(&c->d_ms_head_ctr), sizeof(unsigned int)));
   MS_TRY(hipMemset(c->d_ms_head_ctr, 0, sizeof(unsigned int)));
   c->msnet.head_flag = c->d_ms_head_ctr;
+  c->ms_head_count = 0;
+  if ((rc = alloc_zero(&c->d_ms_hstat, (size_t)c->ms_n_head * S * 2)) != PT_OK) return rc;
+  if ((rc = alloc_zero(&c->d_ms_hpart, (size_t)c->ms_n_head)) != PT_OK) return rc;
+  c->msnet.hstat = c->d_ms_hstat;
+  c->msnet.hpart = c->d_ms_hpart;
   c->msnet.spin_limit = c->spin_limit;
   if ((rc = alloc_zero(&c->d_dummy, (size_t)std::max(kLossSlots, c->out_dim))) != PT_OK) return rc;
   for (int p = 0; p < 2; ++p)
@@ -2363,7 +2382,8 @@ static int run_ticks(partime_ctx *c, const float *x_dev, const void *target_dev,
         a.tgt = i >= c->k ? tgt + (size_t)(i - c->k) * c->tgt_bytes
                           : c->d_hist[c->hist_cur] + (size_t)i * c->tgt_bytes;
       a.loss1 = loss_dev ? loss_dev + i : c->d_dummy;
-      a.seq = (unsigned int)(t + 1);
+      if (learn) c->ms_head_count += (unsigned int)c->ms_n_head;
+      a.seq = c->ms_head_count;
       a.adam_c1 = a.adam_c2 = 0.f;
       if (c->cfg.optimizer == PT_OPT_ADAM) {
         const double n = (double)(t + 1);
@@ -2775,9 +2795,10 @@ int partime_get_tick(partime_ctx *ctx, int64_t *tick) {
 int partime_set_tick(partime_ctx *ctx, int64_t tick) {
   if (!ctx || tick < 0) return fail(PT_EINVAL, "partime_set_tick: bad argument");
   if (ctx->d_ms_head_ctr) {
-    // the loss-head flag holds the sequence number of the last learning tick: it must not match a tick to come
+    // the head-tile counter starts over together with the count the host keeps of it
     HIP_TRY(hipStreamSynchronize(ctx->stream));
     HIP_TRY(hipMemset(ctx->d_ms_head_ctr, 0, sizeof(unsigned int)));
+    ctx->ms_head_count = 0;
   }
   ctx->tick = tick;
   ctx->ms_zp_valid = false;   // which half of the published activations feeds the coming tick depends on its parity
@@ -2797,7 +2818,10 @@ int partime_set_lr(partime_ctx *ctx, float lr) {
 int partime_reset(partime_ctx *ctx) {
   if (!ctx) return fail(PT_EINVAL, "partime_reset: null context");
   HIP_TRY(hipStreamSynchronize(ctx->stream));
-  if (ctx->d_ms_head_ctr) HIP_TRY(hipMemset(ctx->d_ms_head_ctr, 0, sizeof(unsigned int)));
+  if (ctx->d_ms_head_ctr) {
+    HIP_TRY(hipMemset(ctx->d_ms_head_ctr, 0, sizeof(unsigned int)));
+    ctx->ms_head_count = 0;
+  }
   if (ctx->d_head_ctr) {
     HIP_TRY(hipMemset(ctx->d_head_ctr, 0, sizeof(unsigned int)));
     ctx->head_count = 0;
