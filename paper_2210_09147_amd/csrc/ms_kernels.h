@@ -25,6 +25,15 @@
 // outside.  An inference tick writes no weights, so nothing is gained by folding: it is one launch of ms_infer_kernel.
 // rnd() is round-to-nearest-even to bf16: what enters a matrix-core product is bf16, sums are fp32.
 //
+// Several layers per stage (Eq. 3-5: exact back-propagation inside a stage).  Layer j + 1 of a stage needs layer j's output
+// of this tick and layer j's delta needs layer j + 1's input-error of this tick, so a tick becomes a sequence of launches
+// by position in the stage, each over all stages: vector launch of the first layers (their planes come from the previous
+// tick's matrix launch: the fold works for them alone), then for every further position a forward-only matrix launch and
+// a vector launch; the matrix launch of every stage's last layer (with the loss head); then, going back through the
+// positions, a vector launch that forms delta from the pre-activations kept earlier and the error planes the layer
+// behind has just written, and that layer's matrix launch.  Links inside a stage are single buffers of the same tick
+// (both halves of a record's ping-pong pair name the same memory), stage boundaries keep their pairs.
+//
 // Matrix-core operand layout used throughout (16x16x32, D = A * B + C, wave of 64 lanes, lane l, g = l / 16):
 //   A (16 x 32): lane holds A[l % 16][8 g .. 8 g + 7]          (8 bf16 = 16 bytes)
 //   B (32 x 16): lane holds B[8 g .. 8 g + 7][l % 16]
@@ -70,10 +79,12 @@ struct MsStage {
   float *b;                  // [out_pad]
   float *mW, *vW, *mb, *vb;  // Adam moments, fp32, shaped like W and b (NULL under plain SGD)
   int in_dim, out_dim, in_pad, out_pad, act, is_last, is_first;
+  int fold;                  // first layer of its stage: its matrix launch also forms the coming tick's pre-activations
   float *out_act[2];         // [S][out_pad] (NULL: last stage, output goes to the caller)
   float *zp;                 // [n_ct][S][out_pad] partial pre-activations of the coming tick, one plane per column tile
   int n_ct;
-  float *zbuf;               // last stage: [S][out_pad] pre-activations of this tick (the loss head reads them)
+  float *zbuf;               // [S][out_pad] pre-activations of this tick: last layer (the loss head reads them) and layers
+                             // that are not the last of their stage (their delta is formed later in the tick)
   bf16_t *dlt;               // [S][out_pad] delta
   bf16_t *dltT;              // [out_pad][S]
   const bf16_t *xq_in[2];    // rnd(stage input) [S][in_pad], published by the previous stage (NULL: first stage)
@@ -95,7 +106,7 @@ struct MsView {
   bf16_t *W;
   float *b;
   float *mW, *vW, *mb, *vb;
-  int in_dim, out_dim, in_pad, out_pad, act, is_last, is_first;
+  int in_dim, out_dim, in_pad, out_pad, act, is_last, is_first, fold;
   float *out_cur;
   float *zp;
   int n_ct;
@@ -116,7 +127,7 @@ __device__ __forceinline__ MsView ms_view(const MsStage *sp, int cur, int fhalf)
   v.W = sp->W; v.b = sp->b;
   v.mW = sp->mW; v.vW = sp->vW; v.mb = sp->mb; v.vb = sp->vb;
   v.in_dim = sp->in_dim; v.out_dim = sp->out_dim; v.in_pad = sp->in_pad; v.out_pad = sp->out_pad;
-  v.act = sp->act; v.is_last = sp->is_last; v.is_first = sp->is_first;
+  v.act = sp->act; v.is_last = sp->is_last; v.is_first = sp->is_first; v.fold = sp->fold;
   v.out_cur = cur ? sp->out_act[1] : sp->out_act[0];
   v.zp = sp->zp; v.n_ct = sp->n_ct;
   v.zbuf = sp->zbuf; v.dlt = sp->dlt; v.dltT = sp->dltT;
@@ -133,7 +144,9 @@ __device__ __forceinline__ MsView ms_view(const MsStage *sp, int cur, int fhalf)
 }
 
 struct MsTile {
-  int stage, a, b, kind;     // vector kernel: kind 0: rows [a, a + 64); kind 1: columns [a, a + 64) of the first stage's input.
+  int stage, a, b, kind;     // `stage` is the layer's record.  Vector kernel: rows [a, a + 64); kind 0: forward and delta, kind 3:
+                             // forward only, the pre-activations are kept (a layer that is not the last of its stage), kind 4: delta
+                             // from the kept pre-activations; kind 1: columns [a, a + 64) of the first layer's input.
                              // matrix kernel: kind 0: a = row tile, b = column tile; kind 2: loss head, rows [a, a + 64)
 };
 
@@ -255,10 +268,21 @@ __global__ __launch_bounds__(256) void ms_vec_kernel(MsNet net, MsTick a) {
   // a1 (second half of Eq. 6): z = b + the column tiles' shares of W x, summed in a fixed order.  Rows beyond out_dim
   // are padding: their weights and biases are zero, so z = o = 0 there and the padded stores are unconditional.
   const int r = tl.a + 8 * rq;
-  const float4 b0 = ldg_f4(st.b + r), b1 = ldg_f4(st.b + r + 4);
-  float z[8] = {b0.x, b0.y, b0.z, b0.w, b1.x, b1.y, b1.z, b1.w};
   const size_t plane = (size_t)kMsS * st.out_pad;
-  ms_add_planes<8>(st.zp + (size_t)s * st.out_pad + r, st.n_ct, plane, z);
+  const bool fwd = tl.kind != 4, bwd = LEARN && tl.kind != 3;
+  float z[8];
+  if (fwd) {
+    const float4 b0 = ldg_f4(st.b + r), b1 = ldg_f4(st.b + r + 4);
+    z[0] = b0.x; z[1] = b0.y; z[2] = b0.z; z[3] = b0.w; z[4] = b1.x; z[5] = b1.y; z[6] = b1.z; z[7] = b1.w;
+    ms_add_planes<8>(st.zp + (size_t)s * st.out_pad + r, st.n_ct, plane, z);
+    if (tl.kind == 3) {   // a layer that is not the last of its stage: delta needs this tick's z later in the tick (Eq. 9)
+      stg_f4(st.zbuf + (size_t)s * st.out_pad + r, make_float4(z[0], z[1], z[2], z[3]));
+      stg_f4(st.zbuf + (size_t)s * st.out_pad + r + 4, make_float4(z[4], z[5], z[6], z[7]));
+    }
+  } else {
+    const float4 z0 = ldg_f4(st.zbuf + (size_t)s * st.out_pad + r), z1 = ldg_f4(st.zbuf + (size_t)s * st.out_pad + r + 4);
+    z[0] = z0.x; z[1] = z0.y; z[2] = z0.z; z[3] = z0.w; z[4] = z1.x; z[5] = z1.y; z[6] = z1.z; z[7] = z1.w;
+  }
   float o[8];
 #pragma unroll
   for (int j = 0; j < 8; ++j) o[j] = act_fwd(st.act, z[j]);
@@ -293,15 +317,18 @@ __global__ __launch_bounds__(256) void ms_vec_kernel(MsNet net, MsTick a) {
     }
     return;
   }
-  stg_f4(st.out_cur + (size_t)s * st.out_pad + r, make_float4(o[0], o[1], o[2], o[3]));
-  stg_f4(st.out_cur + (size_t)s * st.out_pad + r + 4, make_float4(o[4], o[5], o[6], o[7]));
-  unsigned int po[4], pd[4] = {0u, 0u, 0u, 0u};
+  unsigned int po[4] = {0u, 0u, 0u, 0u}, pd[4] = {0u, 0u, 0u, 0u};
+  if (fwd) {
+    stg_f4(st.out_cur + (size_t)s * st.out_pad + r, make_float4(o[0], o[1], o[2], o[3]));
+    stg_f4(st.out_cur + (size_t)s * st.out_pad + r + 4, make_float4(o[4], o[5], o[6], o[7]));
 #pragma unroll
-  for (int j = 0; j < 4; ++j) po[j] = pack_bf16(o[2 * j], o[2 * j + 1]);
-  stg16(st.xq_cur + (size_t)s * st.out_pad + r, make_uint4(po[0], po[1], po[2], po[3]));
-  if (LEARN) {
-    // a3, a4: g = the error the next stage published one tick earlier (sum of its row-tile planes, Eq. 11),
-    // delta = rnd(g * phi'(z)) with this tick's z (Eq. 9).  Padding rows have z = 0 and g = 0, hence delta = 0.
+    for (int j = 0; j < 4; ++j) po[j] = pack_bf16(o[2 * j], o[2 * j + 1]);
+    stg16(st.xq_cur + (size_t)s * st.out_pad + r, make_uint4(po[0], po[1], po[2], po[3]));
+  }
+  if (bwd) {
+    // a3, a4: g = the error published by the next stage one tick earlier, or by the layer behind in this stage in this
+    // tick (sum of its row-tile planes, Eq. 11 / Eq. 5), delta = rnd(g * phi'(z)) with this tick's z (Eq. 9).
+    // Padding rows have z = 0 and g = 0, hence delta = 0.
     float g[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
     ms_add_planes<4>(st.gin_prev + (size_t)s * st.out_pad + r, st.n_gparts, plane, g);
 #pragma unroll
@@ -319,8 +346,8 @@ __global__ __launch_bounds__(256) void ms_vec_kernel(MsNet net, MsTick a) {
   }
   __syncthreads();
   const int row = tl.a + trow;
-  stg16(st.xT_cur + (size_t)row * kMsS + 8 * tq, *reinterpret_cast<const uint4 *>(&tr[0][trow * kMsS + 8 * tq]));
-  if (LEARN) {
+  if (fwd) stg16(st.xT_cur + (size_t)row * kMsS + 8 * tq, *reinterpret_cast<const uint4 *>(&tr[0][trow * kMsS + 8 * tq]));
+  if (bwd) {
     const uint4 d = *reinterpret_cast<const uint4 *>(&tr[1][trow * kMsS + 8 * tq]);
     stg16(st.dltT + (size_t)row * kMsS + 8 * tq, d);
     // a6 for the bias: b <- b - eta / S * sum over the streams of the rounded delta (what every product sees)
@@ -943,14 +970,17 @@ __global__ __launch_bounds__(64 * kMsNWM) void ms_mat_kernel(MsNet net, MsTick a
     // caches start a launch empty, and nobody reads the last stage's delta in this launch before the flag is up,
     // so no cache on the device can hold a line of it from before the loss head's release.
   }
+  // A layer folds the coming tick's forward product into this launch when it is the first of its stage: its input of the
+  // coming tick is what the stage in front has published in this tick, or the caller's next sample (not there at the last
+  // tick of a call).  The very first layer publishes no error.
+  const bool fold = st.fold && (!st.is_first || a.x_next);
   if (MODE == 1) {
     ms_mat_tile<1, 0, false, true>(net, a, tl, st, zred);
   } else if (!st.is_first) {
-    ms_mat_tile<0, OPT, true, true>(net, a, tl, st, zred);
-  } else if (a.x_next) {
-    ms_mat_tile<0, OPT, false, true>(net, a, tl, st, zred);
+    if (fold) ms_mat_tile<0, OPT, true, true>(net, a, tl, st, zred);
+    else ms_mat_tile<0, OPT, true, false>(net, a, tl, st, zred);
   } else {
-    // the coming tick's input of the first stage is the caller's next sample: not there at the last tick of a call
-    ms_mat_tile<0, OPT, false, false>(net, a, tl, st, zred);
+    if (fold) ms_mat_tile<0, OPT, false, true>(net, a, tl, st, zred);
+    else ms_mat_tile<0, OPT, false, false>(net, a, tl, st, zred);
   }
 }

@@ -1041,10 +1041,14 @@ struct partime_ctx {
   unsigned int ms_head_count = 0;       // what the counter reads once every head tile launched so far is done
   int ms_n_head = 0;                    // head tiles per learning tick
   float *d_ms_hstat = nullptr, *d_ms_hpart = nullptr;
-  int n_tiles_v = 0, n_prep = 0;        // vector launch; its first n_prep tiles round the first stage's input
-  int n_tiles_m = 0;                    // matrix launch of a learning tick (loss head first, last stage's tiles last)
-  int n_tiles_f = 0, n_tiles_f0 = 0;    // forward-only matrix launch, stage by stage; the first n_tiles_f0 are the first stage's
-  int n_tiles_i = 0;                    // inference launch
+  int n_prep = 0;                       // the first n_prep tiles of the first vector launch round the first layer's input
+  int ms_tiles_f_off = 0;
+  int n_tiles_f = 0, n_tiles_f0 = 0;    // forward-only matrix launch over the first layers of all stages; the first
+                                        // n_tiles_f0 are the very first layer's
+  // launches of a tick by position in the stage (offset into the tile array, count), each over all stages:
+  std::vector<std::pair<int, int>> ms_vf, ms_mf, ms_vb, ms_mb, ms_if;   // vector forward [pos], matrix forward-only [pos >= 1],
+                                        // vector backward [back >= 1], matrix learning [back] (back = layers behind it
+                                        // in its stage; [0] carries the loss head), inference [pos]
   bool ms_zp_valid = false;             // the planes of the stages behind the first one are those of the coming tick
   // batched path (64 .. 1024 streams)
   bool rb = false;
@@ -1306,15 +1310,26 @@ int alloc_zero(T **p, size_t n) {
   return PT_OK;
 }
 
-int init_multistream(partime_ctx *c, const float *const *w_host, const float *const *b_host) {
-  const int D = c->depth, S = c->S;
+int init_multistream(partime_ctx *c, const float *const *w_host, const float *const *b_host, const int *balance) {
+  const int D = c->depth, NL = (int)c->layers.size(), S = c->S;
   c->ms = true;
-  c->stages.resize(D);
-  auto pad512 = [](int v) { return (v + kMsTC - 1) / kMsTC * kMsTC; };   // every stage size is padded to whole column tiles
-  for (int h = 0; h < D; ++h) {
-    StageHost &s = c->stages[h];
-    const pt_layer &l = c->layers[h];
-    s.layer = h;
+  c->stages.resize(NL);               // one record per layer; a stage is a run of layers
+  c->first_node.assign(D, 0);
+  c->cmax = 1;
+  for (int h = 0, i = 0; h < D; ++h) {
+    const int cnt = balance ? balance[h] : 1;
+    c->first_node[h] = i;
+    c->cmax = std::max(c->cmax, cnt);
+    for (int j = 0; j < cnt; ++j, ++i) {
+      c->stages[i].stage = h; c->stages[i].pos = j; c->stages[i].cnt = cnt;
+    }
+  }
+  const int cmax = c->cmax;
+  auto pad512 = [](int v) { return (v + kMsTC - 1) / kMsTC * kMsTC; };   // every layer size is padded to whole column tiles
+  for (int i = 0; i < NL; ++i) {
+    StageHost &s = c->stages[i];
+    const pt_layer &l = c->layers[i];
+    s.layer = i;
     s.in_dim = l.in_dim;
     s.out_dim = l.out_dim;
     s.act = l.act;
@@ -1324,32 +1339,39 @@ int init_multistream(partime_ctx *c, const float *const *w_host, const float *co
     s.n_ct = s.in_pad / kMsTC;                     // column tiles = pre-activation planes
     s.act_elems = (size_t)S * s.out_pad;
   }
-  // Tile height of the matrix launch.  A work-group holds one wave per SIMD, so a launch of more tiles than compute units
+  // Tile height of a matrix launch.  A work-group holds one wave per SIMD, so a launch of more tiles than compute units
   // runs in rounds and the last one is rarely full: where taller tiles (fewer error planes as well) make the launch a
-  // single round they are taken.  The last stage keeps the short tiles: they start only once the loss head is done.
-  auto count_tiles = [&](int tr) {
-    int n = 0;   // (the head tiles are not counted: they are gone within a few microseconds)
-    for (int h = 0; h < D; ++h) {
-      const StageHost &s = c->stages[h];
-      const int t = h == D - 1 ? std::min(tr, kMsTR) : tr;
-      n += (s.out_pad + t - 1) / t * s.n_ct;
+  // single round they are taken, per launch.  The last layer keeps the short tiles: they start only once the loss head is
+  // done.  (The head tiles are not counted: they are gone within a few microseconds.)
+  auto back_of = [&](const StageHost &s) { return s.cnt - 1 - s.pos; };
+  for (int back = 0; back < cmax; ++back) {
+    auto count_tiles = [&](int tr) {
+      int n = 0;
+      for (int i = 0; i < NL; ++i) {
+        const StageHost &s = c->stages[i];
+        if (back_of(s) != back) continue;
+        const int t = i == NL - 1 ? std::min(tr, kMsTR) : tr;
+        n += (s.out_pad + t - 1) / t * s.n_ct;
+      }
+      return n;
+    };
+    int tr_all = kMsTR;
+    if (count_tiles(kMsTR) > c->n_cu)
+      for (int tr = 2 * kMsTR; tr <= 8 * kMsTR; tr *= 2)
+        if (count_tiles(tr) <= c->n_cu) { tr_all = tr; break; }
+    for (int i = 0; i < NL; ++i) {
+      StageHost &s = c->stages[i];
+      if (back_of(s) != back) continue;
+      s.tr = i == NL - 1 ? std::min(tr_all, kMsTR) : tr_all;
+      s.n_rt = (s.out_pad + s.tr - 1) / s.tr;        // row tiles = error planes
+      s.n_parts = s.n_rt;
+      s.err_elems = (size_t)s.n_rt * S * s.in_pad;
     }
-    return n;
-  };
-  int tr_all = kMsTR;
-  if (count_tiles(kMsTR) > c->n_cu)
-    for (int tr = 2 * kMsTR; tr <= 8 * kMsTR; tr *= 2)
-      if (count_tiles(tr) <= c->n_cu) { tr_all = tr; break; }
-  for (int h = 0; h < D; ++h) {
-    StageHost &s = c->stages[h];
-    s.tr = h == D - 1 ? std::min(tr_all, kMsTR) : tr_all;
-    s.n_rt = (s.out_pad + s.tr - 1) / s.tr;        // row tiles = error planes
-    s.n_parts = s.n_rt;
-    s.err_elems = (size_t)s.n_rt * S * s.in_pad;
   }
   int rc;
-  for (int h = 0; h < D; ++h) {
-    StageHost &s = c->stages[h];
+  for (int i = 0; i < NL; ++i) {
+    StageHost &s = c->stages[i];
+    const bool last_in_stage = s.pos == s.cnt - 1;
     bf16_t *W = nullptr;
     if ((rc = alloc_zero(&W, (size_t)s.out_pad * s.in_pad)) != PT_OK) return rc;
     s.W = W;
@@ -1360,80 +1382,127 @@ int init_multistream(partime_ctx *c, const float *const *w_host, const float *co
       if ((rc = alloc_zero(&s.mb, (size_t)s.out_pad)) != PT_OK || (rc = alloc_zero(&s.vb, (size_t)s.out_pad)) != PT_OK) return rc;
     }
     if ((rc = alloc_zero(&s.zp, (size_t)s.n_ct * s.act_elems)) != PT_OK) return rc;
-    if (h == D - 1 && (rc = alloc_zero(&s.zbuf, s.act_elems)) != PT_OK) return rc;
+    if ((i == NL - 1 || !last_in_stage) && (rc = alloc_zero(&s.zbuf, s.act_elems)) != PT_OK) return rc;
     if ((rc = alloc_zero(&s.dlt, s.act_elems)) != PT_OK) return rc;
     if ((rc = alloc_zero(&s.dltT, s.act_elems)) != PT_OK) return rc;
-    if (h == 0 && ((rc = alloc_zero(&s.xT0, (size_t)s.in_pad * S)) != PT_OK || (rc = alloc_zero(&s.xq0, (size_t)s.in_pad * S)) != PT_OK)) return rc;
+    if (i == 0 && ((rc = alloc_zero(&s.xT0, (size_t)s.in_pad * S)) != PT_OK || (rc = alloc_zero(&s.xq0, (size_t)s.in_pad * S)) != PT_OK)) return rc;
+    // what a layer publishes crosses a stage boundary as a ping-pong pair; inside a stage it is a single buffer of the
+    // same tick (kept in half 0)
     for (int p = 0; p < 2; ++p) {
-      if (h < D - 1 && (rc = alloc_zero(&s.act_buf[p], s.act_elems)) != PT_OK) return rc;
-      if (h < D - 1 && (rc = alloc_zero(&s.xq[p], s.act_elems)) != PT_OK) return rc;
-      if (h < D - 1 && (rc = alloc_zero(&s.xT[p], s.act_elems)) != PT_OK) return rc;
-      if (h > 0 && (rc = alloc_zero(&s.err_buf[p], s.err_elems)) != PT_OK) return rc;
+      if (i < NL - 1 && (p == 0 || last_in_stage)) {
+        if ((rc = alloc_zero(&s.act_buf[p], s.act_elems)) != PT_OK) return rc;
+        if ((rc = alloc_zero(&s.xq[p], s.act_elems)) != PT_OK) return rc;
+        if ((rc = alloc_zero(&s.xT[p], s.act_elems)) != PT_OK) return rc;
+      }
+      if (i > 0 && (p == 0 || s.pos == 0) && (rc = alloc_zero(&s.err_buf[p], s.err_elems)) != PT_OK) return rc;
     }
-    if ((rc = upload_weights(c, h, w_host[h], b_host[h])) != PT_OK) return rc;
+    if ((rc = upload_weights(c, i, w_host[i], b_host[i])) != PT_OK) return rc;
   }
-  std::vector<MsStage> sd(D);
-  std::vector<MsTile> tv, tm, tm_last, tf, ti;
-  for (int k0 = 0; k0 < c->stages[0].in_pad; k0 += kMsVR) tv.push_back(MsTile{0, k0, 0, 1});   // the input of the first stage
-  c->n_prep = (int)tv.size();
-  for (int h = 0; h < D; ++h) {
-    StageHost &s = c->stages[h];
-    MsStage &d = sd[h];
+  auto half = [](auto *const (&pair)[2], int p) { return pair[p] ? pair[p] : pair[0]; };
+  std::vector<MsStage> sd(NL);
+  for (int i = 0; i < NL; ++i) {
+    StageHost &s = c->stages[i];
+    MsStage &d = sd[i];
     std::memset(&d, 0, sizeof d);
     d.W = static_cast<bf16_t *>(s.W);
     d.b = s.b;
     d.mW = s.mW; d.vW = s.vW; d.mb = s.mb; d.vb = s.vb;
     d.in_dim = s.in_dim; d.out_dim = s.out_dim; d.in_pad = s.in_pad; d.out_pad = s.out_pad;
-    d.act = s.act; d.is_last = h == D - 1; d.is_first = h == 0;
+    d.act = s.act; d.is_last = i == NL - 1; d.is_first = i == 0; d.fold = s.pos == 0;
     d.zp = s.zp; d.n_ct = s.n_ct;
     d.zbuf = s.zbuf; d.dlt = s.dlt; d.dltT = s.dltT; d.xT0 = s.xT0; d.xq0 = s.xq0;
     for (int p = 0; p < 2; ++p) {
-      d.out_act[p] = s.act_buf[p];
-      d.xq_in[p] = h > 0 ? c->stages[h - 1].xq[p] : nullptr;
-      d.xq_out[p] = s.xq[p];
-      d.xT_in[p] = h > 0 ? c->stages[h - 1].xT[p] : nullptr;
-      d.xT_out[p] = s.xT[p];
-      d.gin[p] = h < D - 1 ? c->stages[h + 1].err_buf[p] : nullptr;
-      d.eout[p] = s.err_buf[p];
+      d.out_act[p] = half(s.act_buf, p);
+      d.xq_in[p] = i > 0 ? half(c->stages[i - 1].xq, p) : nullptr;
+      d.xq_out[p] = half(s.xq, p);
+      d.xT_in[p] = i > 0 ? half(c->stages[i - 1].xT, p) : nullptr;
+      d.xT_out[p] = half(s.xT, p);
+      d.gin[p] = i < NL - 1 ? half(c->stages[i + 1].err_buf, p) : nullptr;
+      d.eout[p] = half(s.err_buf, p);
     }
-    d.n_gparts = h < D - 1 ? c->stages[h + 1].n_rt : 0;
+    d.n_gparts = i < NL - 1 ? c->stages[i + 1].n_rt : 0;
     d.n_rt = s.n_rt; d.tr = s.tr;
-    for (int r = 0; r < s.out_pad; r += kMsVR) tv.push_back(MsTile{h, r, 0, 0});
-    for (int r = 0; r < s.out_pad; r += kMsRowsF) ti.push_back(MsTile{h, r, kMsRowsF, 0});
-    std::vector<MsTile> &dst = h == D - 1 ? tm_last : tm;
+  }
+  // tile lists, one per launch
+  std::vector<MsTile> all;
+  auto close_list = [&](std::vector<std::pair<int, int>> &lists, int at) {
+    if ((int)lists.size() <= at) lists.resize(at + 1, {(int)all.size(), 0});
+    lists[at].second = (int)all.size() - lists[at].first;
+  };
+  auto open_list = [&](std::vector<std::pair<int, int>> &lists, int at) {
+    if ((int)lists.size() <= at) lists.resize(at + 1);
+    lists[at] = {(int)all.size(), 0};
+  };
+  auto mat_tiles = [&](int i) {
+    const StageHost &s = c->stages[i];
     for (int p = 0; p < s.n_rt; ++p)
-      for (int q = 0; q < s.n_ct; ++q) {
-        dst.push_back(MsTile{h, p, q, 0});
-        tf.push_back(MsTile{h, p, q, 0});
+      for (int q = 0; q < s.n_ct; ++q) all.push_back(MsTile{i, p, q, 0});
+  };
+  for (int pos = 0; pos < cmax; ++pos) {
+    // vector launch of the layers at this position: forward and delta for a stage's last layer (its error signal is one
+    // tick old, or comes from the loss head), forward alone otherwise
+    open_list(c->ms_vf, pos);
+    if (pos == 0) {
+      for (int k0 = 0; k0 < c->stages[0].in_pad; k0 += kMsVR) all.push_back(MsTile{0, k0, 0, 1});   // the input of the first layer
+      c->n_prep = (int)all.size() - c->ms_vf[0].first;
+    }
+    for (int i = 0; i < NL; ++i) {
+      const StageHost &s = c->stages[i];
+      if (s.pos != pos) continue;
+      for (int r = 0; r < s.out_pad; r += kMsVR) all.push_back(MsTile{i, r, 0, s.pos == s.cnt - 1 ? 0 : 3});
+    }
+    close_list(c->ms_vf, pos);
+    open_list(c->ms_mf, pos);
+    if (pos > 0)
+      for (int i = 0; i < NL; ++i)
+        if (c->stages[i].pos == pos) mat_tiles(i);
+    close_list(c->ms_mf, pos);
+    open_list(c->ms_if, pos);
+    for (int i = 0; i < NL; ++i) {
+      const StageHost &s = c->stages[i];
+      if (s.pos != pos) continue;
+      for (int r = 0; r < s.out_pad; r += kMsRowsF) all.push_back(MsTile{i, r, kMsRowsF, 0});
+    }
+    close_list(c->ms_if, pos);
+  }
+  for (int back = 0; back < cmax; ++back) {
+    open_list(c->ms_vb, back);
+    if (back > 0)
+      for (int i = 0; i < NL; ++i) {
+        const StageHost &s = c->stages[i];
+        if (back_of(s) != back) continue;
+        for (int r = 0; r < s.out_pad; r += kMsVR) all.push_back(MsTile{i, r, 0, 4});
       }
-    if (h == 0) c->n_tiles_f0 = (int)tf.size();
+    close_list(c->ms_vb, back);
+    // matrix launch of a learning tick; the first one carries the loss head of the last layer in front and the last
+    // layer's own tiles (which wait for the delta it provides) at its end
+    open_list(c->ms_mb, back);
+    if (back == 0) {
+      for (int r = 0; r < c->stages[NL - 1].out_pad; r += kMsVR) all.push_back(MsTile{NL - 1, r, kMsVR, 2});
+      c->ms_n_head = (int)all.size() - c->ms_mb[0].first;
+    }
+    for (int i = 0; i < NL; ++i)
+      if (back_of(c->stages[i]) == back && i != NL - 1) mat_tiles(i);
+    if (back == 0) mat_tiles(NL - 1);
+    close_list(c->ms_mb, back);
   }
-  // matrix launch of a learning tick: the loss head of the last stage first, the last stage's own tiles (which wait
-  // for the delta it provides) last
   {
-    std::vector<MsTile> heads;
-    for (int r = 0; r < c->stages[D - 1].out_pad; r += kMsVR) heads.push_back(MsTile{D - 1, r, kMsVR, 2});
-    c->ms_n_head = (int)heads.size();
-    tm.insert(tm.begin(), heads.begin(), heads.end());
+    // forward-only matrix launch for the planes a folded pass could not form: the very first layer's, then the other
+    // stages' first layers
+    const int at = (int)all.size();
+    mat_tiles(0);
+    c->n_tiles_f0 = (int)all.size() - at;
+    for (int i = 1; i < NL; ++i)
+      if (c->stages[i].pos == 0) mat_tiles(i);
+    c->n_tiles_f = (int)all.size() - at;
+    c->ms_tiles_f_off = at;
   }
-  tm.insert(tm.end(), tm_last.begin(), tm_last.end());
-  c->n_tiles_v = (int)tv.size();
-  c->n_tiles_m = (int)tm.size();
-  c->n_tiles_f = (int)tf.size();
-  c->n_tiles_i = (int)ti.size();
-  std::vector<MsTile> all(tv);
-  all.insert(all.end(), tm.begin(), tm.end());
-  all.insert(all.end(), tf.begin(), tf.end());
-  all.insert(all.end(), ti.begin(), ti.end());
-  MS_TRY(hipMalloc(reinterpret_cast<void **>(&c->d_ms_stages), sizeof(MsStage) * D));
-  MS_TRY(hipMemcpy(c->d_ms_stages, sd.data(), sizeof(MsStage) * D, hipMemcpyHostToDevice));
+  MS_TRY(hipMalloc(reinterpret_cast<void **>(&c->d_ms_stages), sizeof(MsStage) * NL));
+  MS_TRY(hipMemcpy(c->d_ms_stages, sd.data(), sizeof(MsStage) * NL, hipMemcpyHostToDevice));
   MS_TRY(hipMalloc(reinterpret_cast<void **>(&c->d_ms_tiles), sizeof(MsTile) * all.size()));
   MS_TRY(hipMemcpy(c->d_ms_tiles, all.data(), sizeof(MsTile) * all.size(), hipMemcpyHostToDevice));
   c->msnet.stages = c->d_ms_stages;
-  c->msnet.tiles_v = c->d_ms_tiles;
-  c->msnet.tiles_m = c->d_ms_tiles + tv.size();
-  c->msnet.tiles_f = c->d_ms_tiles + tv.size() + tm.size();
-  c->msnet.tiles_i = c->d_ms_tiles + tv.size() + tm.size() + tf.size();
+  c->msnet.tiles_v = c->msnet.tiles_m = c->msnet.tiles_f = c->msnet.tiles_i = c->d_ms_tiles;   // set per launch
   c->msnet.loss = c->cfg.loss;
   c->msnet.out_dim = c->out_dim;
   c->msnet.lr_over_s = c->lr / (float)S;
@@ -1953,8 +2022,6 @@ int partime_init(const partime_config *cfg, const float *const *w_host, const fl
     for (int q = 0; q < i; ++q)
       if (cfg->layers[q].skip_from == sf) return fail(PT_EUNSUPPORTED, "partime_init: layer %d is the source of two skips", sf);
   }
-  if (cfg->depth != cfg->n_layers && cfg->n_streams != 1 && cfg->n_streams < 64)
-    return fail(PT_EUNSUPPORTED, "partime_init: several layers per stage are built for pipelines of one stream or of 64 and more");
   if (cfg->optimizer != PT_OPT_SGD && cfg->optimizer != PT_OPT_ADAM) return fail(PT_EINVAL, "partime_init: bad optimizer");
   if (cfg->optimizer == PT_OPT_ADAM) {
     if (cfg->exec_mode == PT_EXEC_PERSISTENT)
@@ -2021,7 +2088,7 @@ int partime_init(const partime_config *cfg, const float *const *w_host, const fl
     return PT_OK;
   }
   if (c->S > 1) {
-    int rcm = init_multistream(c, w_host, b_host);
+    int rcm = init_multistream(c, w_host, b_host, cfg->balance);
     if (rcm != PT_OK) return bail(rcm);
     *out = c;
     g_err[0] = 0;
@@ -2357,16 +2424,37 @@ static int run_ticks(partime_ctx *c, const float *x_dev, const void *target_dev,
     // the pre-activation planes of tick t + 1.  What it could not form (the first stage's at the last tick of the previous
     // call: the caller's next sample was not known; everything after inference ticks or after the state was changed from
     // outside) is formed here first by a forward-only matrix launch.  An inference tick is one launch of its own kernel.
+    MsNet net = c->msnet;
+    auto vec = [&](bool lrn, const std::pair<int, int> &l, int count, const MsTick &a) {
+      if (count <= 0) return;
+      net.tiles_v = c->d_ms_tiles + l.first;
+      if (lrn) hipLaunchKernelGGL(ms_vec_kernel<true>, dim3(count), dim3(256), 0, c->stream, net, a);
+      else hipLaunchKernelGGL(ms_vec_kernel<false>, dim3(count), dim3(256), 0, c->stream, net, a);
+      ++c->last_launches;
+    };
+    auto mat_fwd = [&](int off, int count, const MsTick &a) {
+      if (count <= 0) return;
+      net.tiles_f = c->d_ms_tiles + off;
+      hipLaunchKernelGGL((ms_mat_kernel<1, 0>), dim3(count), dim3(64 * kMsNWM), 0, c->stream, net, a);
+      ++c->last_launches;
+    };
+    auto mat_learn = [&](const std::pair<int, int> &l, const MsTick &a) {
+      if (l.second <= 0) return;
+      net.tiles_m = c->d_ms_tiles + l.first;
+      if (c->cfg.optimizer == PT_OPT_ADAM)
+        hipLaunchKernelGGL((ms_mat_kernel<0, 1>), dim3(l.second), dim3(64 * kMsNWM), 0, c->stream, net, a);
+      else
+        hipLaunchKernelGGL((ms_mat_kernel<0, 0>), dim3(l.second), dim3(64 * kMsNWM), 0, c->stream, net, a);
+      ++c->last_launches;
+    };
     if (learn) {
       MsTick a{};
       a.x = x_dev;
       a.x_next = x_dev;                       // the prep tiles round "the coming tick's" samples: here this tick's
       a.cur = (int)(c->tick & 1);
       a.fhalf = a.cur ^ 1;                    // inputs of tick t are what the stages published at tick t - 1
-      hipLaunchKernelGGL(ms_vec_kernel<false>, dim3(c->n_prep), dim3(256), 0, c->stream, c->msnet, a);
-      const int nf = c->ms_zp_valid ? c->n_tiles_f0 : c->n_tiles_f;
-      hipLaunchKernelGGL((ms_mat_kernel<1, 0>), dim3(nf), dim3(64 * kMsNWM), 0, c->stream, c->msnet, a);
-      c->last_launches += 2;
+      vec(false, c->ms_vf[0], c->n_prep, a);
+      mat_fwd(c->ms_tiles_f_off, c->ms_zp_valid ? c->n_tiles_f0 : c->n_tiles_f, a);
     }
     for (int i = 0; i < n_ticks; ++i) {
       const int64_t t = c->tick + i;
@@ -2391,15 +2479,27 @@ static int run_ticks(partime_ctx *c, const float *x_dev, const void *target_dev,
         a.adam_c2 = (float)(1.0 / std::sqrt(1.0 - std::pow((double)c->cfg.beta2, n)));
       }
       if (learn) {
-        hipLaunchKernelGGL(ms_vec_kernel<true>, dim3(c->n_tiles_v), dim3(256), 0, c->stream, c->msnet, a);
-        if (c->cfg.optimizer == PT_OPT_ADAM)
-          hipLaunchKernelGGL((ms_mat_kernel<0, 1>), dim3(c->n_tiles_m), dim3(64 * kMsNWM), 0, c->stream, c->msnet, a);
-        else
-          hipLaunchKernelGGL((ms_mat_kernel<0, 0>), dim3(c->n_tiles_m), dim3(64 * kMsNWM), 0, c->stream, c->msnet, a);
-        c->last_launches += 2;
+        // forward through the positions of a stage: the planes of the first layers were left by the previous tick's matrix
+        // launch, those of the others are formed now, after the layer in front has published its output of this tick
+        for (int pos = 0; pos < c->cmax; ++pos) {
+          MsTick f = a;
+          f.fhalf = a.cur ^ 1;                // (within a stage both halves name the same buffer)
+          if (pos > 0) mat_fwd(c->ms_mf[pos].first, c->ms_mf[pos].second, f);
+          vec(true, c->ms_vf[pos], c->ms_vf[pos].second, a);
+        }
+        // backward: every stage's last layer first, then the layers in front of it, each after the layer behind it has
+        // left its input-error of this tick
+        for (int back = 0; back < c->cmax; ++back) {
+          if (back > 0) vec(true, c->ms_vb[back], c->ms_vb[back].second, a);
+          mat_learn(c->ms_mb[back], a);
+        }
       } else {
-        hipLaunchKernelGGL(ms_infer_kernel, dim3(c->n_tiles_i), dim3(256), 0, c->stream, c->msnet, a);
-        c->last_launches += 1;
+        for (int pos = 0; pos < c->cmax; ++pos) {
+          if (c->ms_if[pos].second <= 0) continue;
+          net.tiles_i = c->d_ms_tiles + c->ms_if[pos].first;
+          hipLaunchKernelGGL(ms_infer_kernel, dim3(c->ms_if[pos].second), dim3(256), 0, c->stream, net, a);
+          ++c->last_launches;
+        }
       }
     }
     c->ms_zp_valid = learn;   // (an inference tick forms no planes for the tick after it)
@@ -2654,9 +2754,8 @@ int partime_get_buffer(partime_ctx *ctx, int which, int stage, int half, float *
     return PT_OK;
   }
   // dense single-stream path: a stage's activation is its last layer's, its error its first layer's
-  StageHost &s = ctx->ms ? ctx->stages[stage]
-                         : ctx->stages[which == 0 ? ctx->first_node[stage] + ctx->stages[ctx->first_node[stage]].cnt - 1
-                                                  : ctx->first_node[stage]];
+  StageHost &s = ctx->stages[which == 0 ? ctx->first_node[stage] + ctx->stages[ctx->first_node[stage]].cnt - 1
+                                       : ctx->first_node[stage]];
   if (ctx->rb) {
     // activations live as bf16 [S][out_pad] (what the next stage's products read), errors as fp32 [S][in_pad]
     StageHost &r = s;   // activation: the stage's last layer; error: its first layer
@@ -2729,9 +2828,8 @@ int partime_set_buffer(partime_ctx *ctx, int which, int stage, int half, const f
     }
     return PT_OK;
   }
-  StageHost &s = ctx->ms ? ctx->stages[stage]
-                         : ctx->stages[which == 0 ? ctx->first_node[stage] + ctx->stages[ctx->first_node[stage]].cnt - 1
-                                                  : ctx->first_node[stage]];
+  StageHost &s = ctx->stages[which == 0 ? ctx->first_node[stage] + ctx->stages[ctx->first_node[stage]].cnt - 1
+                                       : ctx->first_node[stage]];
   if (ctx->rb) {
     StageHost &r = s;   // activation: the stage's last layer; error: its first layer
     const int S = ctx->S;

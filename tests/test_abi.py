@@ -86,7 +86,6 @@ def test_init_rejects_unsupported_combinations_on_the_host():
         (good, dict(n_streams=48, w_dtype=B.PT_BF16), B.PT_EUNSUPPORTED),     # neither 32 nor a multiple of 64
         (good, dict(n_streams=2048, w_dtype=B.PT_BF16), B.PT_EUNSUPPORTED),   # beyond the largest batch
         (good, dict(n_streams=64), B.PT_EUNSUPPORTED),                         # several streams take bf16 weights
-        (good, dict(n_streams=32, w_dtype=B.PT_BF16, balance=[2, 1]), B.PT_EUNSUPPORTED),   # 32 streams: one layer per stage
         (good, dict(adam=(1.0, 0.999, 1e-8)), B.PT_EINVAL),
         (good, dict(adam=(0.9, 0.999, 0.0)), B.PT_EINVAL),
         (good, dict(adam=adam, exec_mode=B.PT_EXEC_PERSISTENT), B.PT_EUNSUPPORTED),

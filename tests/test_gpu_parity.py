@@ -394,6 +394,47 @@ def test_multistream_adam(loss):
              min_move=2e-2, negative=True)
 
 
+@pytest.mark.parametrize("balance", [[5], [2, 3], [3, 1, 1], [1, 2, 2]])
+@pytest.mark.parametrize("adam", [None, (0.9, 0.999, 1e-8)])
+def test_multistream_several_layers_per_stage(balance, adam):
+    """Exact back-propagation inside a stage (Eq. 3-5) on the 32-stream path: the fold across the tick boundary works
+    for the first layer of a stage alone, the others take a forward-only matrix launch; one stage is plain SGD / Adam
+    over 32 samples."""
+    w = ms_workload([100, 260, 130, 600, 140, 10], ps.ACT_GELU, ps.LOSS_CE, lr=2e-3 if adam else 0.05, drift=0.05, seed=15,
+                    balance=balance)
+    run_pair(w, 14, bf16=True, adam=adam, negative=True)
+    run_pair(w, 14, bf16=True, adam=adam, pipes=[{}, {"chunks": [(0, 1), (1, 6), (6, 14)]}], k=0, return_weights=True)
+
+
+def test_multistream_several_layers_per_stage_relu_mse_infer():
+    w = ms_workload([96, 160, 1100, 80, 12], ps.ACT_RELU, ps.LOSS_MSE, lr=0.05, drift=0.05, seed=16, balance=[2, 2])
+    run_pair(w, 12, bf16=True, negative=True)
+    Ws, bs = ps.init_weights(w.layers, w.seed)
+    x, tg = ps.make_inputs(w, 20)
+    ref = orc.Oracle(w.layers, Ws, bs, loss=w.loss, lr=w.lr, n_streams=32, w_bf16=True, operands_bf16=True, balance=w.balance)
+    p = Pipeline(w.layers, Ws, bs, loss=w.loss, lr=w.lr, n_streams=32, w_dtype=B.PT_BF16, balance=w.balance)
+    xd, td = torch.from_numpy(x).cuda(), torch.from_numpy(tg).cuda()
+    # learning, inference, learning again: the planes formed ahead of a tick are stale after the inference ticks
+    t = 0
+    for kind, n in [("L", 5), ("I", 3), ("L", 1), ("L", 4), ("I", 1), ("L", 6)]:
+        if kind == "L":
+            ro, _ = ref.step(x[t:t + n], tg[t:t + n])
+            o, _ = p.step(xd[t:t + n], td[t:t + n])
+        else:
+            ro = ref.infer(x[t:t + n])
+            o = p.infer(xd[t:t + n])
+        o = o.cpu().numpy()
+        for i in range(n):
+            if t + i >= 1:
+                assert rel(o[i], ro[i]) < BF16_TOL, (kind, t + i, rel(o[i], ro[i]))
+        t += n
+    for i in range(len(w.layers)):
+        W, b = p.weights(i)
+        W0, b0 = ref.get_weights(i)
+        assert rel(W - Ws[i], W0 - Ws[i]) < 5 * BF16_TOL, (i, rel(W - Ws[i], W0 - Ws[i]))
+    p.close()
+
+
 def test_config4_full_size_multistream():
     """8 x 4096-wide bf16 layers (last 4096 -> 1000), 32 streams, at full size.  A tick of the plain-loop oracle is
     about 25 GFLOP here, so the pipeline is not filled tick by tick: it starts from a synthetic full state."""
