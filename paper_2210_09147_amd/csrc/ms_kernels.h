@@ -97,6 +97,15 @@ struct MsStage {
   int n_gparts;
   float *eout[2];            // this stage's error planes [n_rt][S][in_pad] (NULL for the first stage)
   int n_rt, tr;              // row tiles of the matrix launch (= error planes) and their height
+  // skip connections (Sec. V-C): a layer that adds the output of an earlier layer reads it with the delay of the stage
+  // boundaries in between and hands the gradient at its own output back with the same delay.  Both wait in rings of
+  // d + 1 slots of fp32 [S][out_pad], slot = tick mod (d + 1); the rings belong to the target.
+  const float *skip_in;      // target: ring of the source's outputs
+  float *serr_out;           // target: ring of gradients for the source
+  int skip_n, skip_d;        // target: slots, delay
+  float *skip_out;           // source: the ring it writes its output to ...
+  const float *serr_in;      // ... and the ring it reads its extra gradient from
+  int src_n, src_d;
 };
 
 // what one tick of one stage needs, with the ping-pong halves already chosen: plain scalars and pointers, so the
@@ -121,8 +130,10 @@ struct MsView {
   int n_gparts;
   float *eout_cur;
   int n_rt, tr;
+  const float *skip_in, *serr_in;   // ring slots of this tick, already chosen (NULL: no skip)
+  float *skip_out, *serr_out;
 };
-__device__ __forceinline__ MsView ms_view(const MsStage *sp, int cur, int fhalf) {
+__device__ __forceinline__ MsView ms_view(const MsStage *sp, int cur, int fhalf, int tick = 0) {
   MsView v;
   v.W = sp->W; v.b = sp->b;
   v.mW = sp->mW; v.vW = sp->vW; v.mb = sp->mb; v.vb = sp->vb;
@@ -140,6 +151,11 @@ __device__ __forceinline__ MsView ms_view(const MsStage *sp, int cur, int fhalf)
   v.n_gparts = sp->n_gparts;
   v.eout_cur = cur ? sp->eout[1] : sp->eout[0];
   v.n_rt = sp->n_rt; v.tr = sp->tr;
+  const size_t slot = (size_t)kMsS * sp->out_pad;
+  v.skip_in = sp->skip_in ? sp->skip_in + (size_t)((tick + sp->skip_n - sp->skip_d) % sp->skip_n) * slot : nullptr;
+  v.serr_out = sp->serr_out ? sp->serr_out + (size_t)(tick % sp->skip_n) * slot : nullptr;
+  v.skip_out = sp->skip_out ? sp->skip_out + (size_t)(tick % sp->src_n) * slot : nullptr;
+  v.serr_in = sp->serr_in ? sp->serr_in + (size_t)((tick + sp->src_n - sp->src_d) % sp->src_n) * slot : nullptr;
   return v;
 }
 
@@ -170,6 +186,7 @@ struct MsTick {
   float *out;           // [S][out_dim]
   float *loss1;
   int cur, learn;
+  int tick;             // tick number modulo the common period of all skip rings: their slots
   int fhalf;            // which half of the published activations the forward product of this launch reads
   unsigned int seq;     // what head_flag reads once every head tile of this tick is done
   float adam_c1, adam_c2;   // lr / (1 - beta1^n), 1 / sqrt(1 - beta2^n)
@@ -229,7 +246,7 @@ template <bool LEARN>
 __global__ __launch_bounds__(256) void ms_vec_kernel(MsNet net, MsTick a) {
   __shared__ __attribute__((aligned(16))) unsigned short tr[2][kMsVR * kMsS];   // bf16 [row][stream]: outputs, deltas
   const MsTile tl = net.tiles_v[blockIdx.x];
-  const MsView st = ms_view(net.stages + tl.stage, a.cur, a.cur);
+  const MsView st = ms_view(net.stages + tl.stage, a.cur, a.cur, a.tick);
   const int tid = threadIdx.x, s = tid >> 3, rq = tid & 7;
   const int trow = tid >> 2, tq = tid & 3;           // transposed phase: row of the tile, group of 8 streams
 
@@ -286,6 +303,15 @@ __global__ __launch_bounds__(256) void ms_vec_kernel(MsNet net, MsTick a) {
   float o[8];
 #pragma unroll
   for (int j = 0; j < 8; ++j) o[j] = act_fwd(st.act, z[j]);
+  if (fwd && st.skip_in) {
+    // the skipped tensor is added after the activation
+    const float4 s0 = ldg_f4(st.skip_in + (size_t)s * st.out_pad + r), s1 = ldg_f4(st.skip_in + (size_t)s * st.out_pad + r + 4);
+    o[0] += s0.x; o[1] += s0.y; o[2] += s0.z; o[3] += s0.w; o[4] += s1.x; o[5] += s1.y; o[6] += s1.z; o[7] += s1.w;
+  }
+  if (fwd && st.skip_out) {
+    stg_f4(st.skip_out + (size_t)s * st.out_pad + r, make_float4(o[0], o[1], o[2], o[3]));
+    stg_f4(st.skip_out + (size_t)s * st.out_pad + r + 4, make_float4(o[4], o[5], o[6], o[7]));
+  }
   if (st.is_last) {
 #pragma unroll
     for (int j = 0; j < 8; ++j)
@@ -331,6 +357,14 @@ __global__ __launch_bounds__(256) void ms_vec_kernel(MsNet net, MsTick a) {
     // Padding rows have z = 0 and g = 0, hence delta = 0.
     float g[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
     ms_add_planes<4>(st.gin_prev + (size_t)s * st.out_pad + r, st.n_gparts, plane, g);
+    if (st.serr_in) {    // source of a skip: the delayed gradient of the target joins
+      const float4 e0 = ldg_f4(st.serr_in + (size_t)s * st.out_pad + r), e1 = ldg_f4(st.serr_in + (size_t)s * st.out_pad + r + 4);
+      g[0] += e0.x; g[1] += e0.y; g[2] += e0.z; g[3] += e0.w; g[4] += e1.x; g[5] += e1.y; g[6] += e1.z; g[7] += e1.w;
+    }
+    if (st.serr_out) {   // target of a skip: the gradient at its output goes back unchanged
+      stg_f4(st.serr_out + (size_t)s * st.out_pad + r, make_float4(g[0], g[1], g[2], g[3]));
+      stg_f4(st.serr_out + (size_t)s * st.out_pad + r + 4, make_float4(g[4], g[5], g[6], g[7]));
+    }
 #pragma unroll
     for (int j = 0; j < 4; ++j) pd[j] = pack_bf16(g[2 * j] * act_der(st.act, z[2 * j]), g[2 * j + 1] * act_der(st.act, z[2 * j + 1]));
     stg16(st.dlt + (size_t)s * st.out_pad + r, make_uint4(pd[0], pd[1], pd[2], pd[3]));
@@ -375,7 +409,7 @@ __global__ __launch_bounds__(256) void ms_infer_kernel(MsNet net, MsTick a) {
   constexpr int NB = kMsRW / 16;   // 16-row blocks per wave
   __shared__ __attribute__((aligned(16))) unsigned short xs[2][kMsS * kMsXPitch];
   const MsTile tl = net.tiles_i[blockIdx.x];
-  const MsView st = ms_view(net.stages + tl.stage, a.cur, a.cur ^ 1);
+  const MsView st = ms_view(net.stages + tl.stage, a.cur, a.cur ^ 1, a.tick);
   const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6, li = lane & 15, g = lane >> 4;
   const bf16_t *xq = st.is_first ? nullptr : st.xq_fwd;   // what the stage in front published one tick earlier
   const int r0 = tl.a + kMsRW * wv;                    // out_pad is a multiple of the tile: always in range
@@ -518,6 +552,11 @@ __global__ __launch_bounds__(256) void ms_infer_kernel(MsNet net, MsTick a) {
       float o[4];
 #pragma unroll
       for (int j = 0; j < 4; ++j) o[j] = act_fwd(st.act, acc[b][h][j] + bb[j]);
+      if (st.skip_in) {
+        const float4 sk = ldg_f4(st.skip_in + (size_t)s * st.out_pad + rb);
+        o[0] += sk.x; o[1] += sk.y; o[2] += sk.z; o[3] += sk.w;
+      }
+      if (st.skip_out) stg_f4(st.skip_out + (size_t)s * st.out_pad + rb, make_float4(o[0], o[1], o[2], o[3]));
       if (st.is_last) {
 #pragma unroll
         for (int j = 0; j < 4; ++j)

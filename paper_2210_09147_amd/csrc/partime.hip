@@ -1396,6 +1396,14 @@ int init_multistream(partime_ctx *c, const float *const *w_host, const float *co
       }
       if (i > 0 && (p == 0 || s.pos == 0) && (rc = alloc_zero(&s.err_buf[p], s.err_elems)) != PT_OK) return rc;
     }
+    if (c->layers[i].skip_from >= 0) {
+      // target of a skip: the rings of the skipped tensor and of its gradient, one slot per tick of delay and one more
+      s.skip_delay = s.stage - c->stages[c->layers[i].skip_from].stage;
+      const size_t n = (size_t)(s.skip_delay + 1) * S * s.out_pad;
+      s.ring_bytes = n * 4;
+      if ((rc = alloc_zero(&s.skip_ring, n)) != PT_OK || (rc = alloc_zero(&s.serr_ring, n)) != PT_OK) return rc;
+      if ((rc = add_ring_length(c, s.skip_delay + 1)) != PT_OK) return rc;
+    }
     if ((rc = upload_weights(c, i, w_host[i], b_host[i])) != PT_OK) return rc;
   }
   auto half = [](auto *const (&pair)[2], int p) { return pair[p] ? pair[p] : pair[0]; };
@@ -1422,6 +1430,14 @@ int init_multistream(partime_ctx *c, const float *const *w_host, const float *co
     }
     d.n_gparts = i < NL - 1 ? c->stages[i + 1].n_rt : 0;
     d.n_rt = s.n_rt; d.tr = s.tr;
+    if (s.skip_ring) {
+      d.skip_in = s.skip_ring; d.serr_out = s.serr_ring; d.skip_n = s.skip_delay + 1; d.skip_d = s.skip_delay;
+    }
+    for (int t = i + 1; t < NL; ++t)
+      if (c->layers[t].skip_from == i) {   // the layer that adds this layer's output
+        const StageHost &q = c->stages[t];
+        d.skip_out = q.skip_ring; d.serr_in = q.serr_ring; d.src_n = q.skip_delay + 1; d.src_d = q.skip_delay;
+      }
   }
   // tile lists, one per launch
   std::vector<MsTile> all;
@@ -2014,8 +2030,8 @@ int partime_init(const partime_config *cfg, const float *const *w_host, const fl
     const int sf = cfg->layers[i].skip_from;
     if (sf < -1 || sf >= i) return fail(PT_EINVAL, "partime_init: layer %d: skip_from must name an earlier layer or be -1", i);
     if (sf < 0) continue;
-    if ((cfg->n_streams != 1 && cfg->n_streams < 64) || cfg->exec_mode == PT_EXEC_PERSISTENT)
-      return fail(PT_EUNSUPPORTED, "partime_init: skip connections are built for pipelines of one stream or of 64 and more, launch per tick");
+    if (cfg->exec_mode == PT_EXEC_PERSISTENT)
+      return fail(PT_EUNSUPPORTED, "partime_init: skip connections take one launch per tick, not the persistent kernel");
     if (i == cfg->n_layers - 1) return fail(PT_EUNSUPPORTED, "partime_init: the last layer cannot be the target of a skip");
     if (!any_conv && cfg->layers[sf].out_dim != cfg->layers[i].out_dim)
       return fail(PT_ESHAPE, "partime_init: layer %d adds the output of layer %d: %d != %d", i, sf, cfg->layers[i].out_dim, cfg->layers[sf].out_dim);
@@ -2463,6 +2479,7 @@ static int run_ticks(partime_ctx *c, const float *x_dev, const void *target_dev,
       a.x_next = i + 1 < n_ticks ? a.x + (size_t)c->S * c->in_dim : nullptr;
       a.out = out_dev + (size_t)i * c->S * c->out_dim;
       a.cur = (int)(t & 1);
+      a.tick = (int)(t % c->ring_period);
       a.fhalf = a.cur;                        // inputs of tick t + 1 are what the stages publish in this tick
       a.learn = learn && t >= c->fill && c->cfg.loss != PT_LOSS_NONE;
       a.tgt = nullptr;

@@ -91,7 +91,6 @@ def test_init_rejects_unsupported_combinations_on_the_host():
         (good, dict(adam=adam, exec_mode=B.PT_EXEC_PERSISTENT), B.PT_EUNSUPPORTED),
         (skip(1, 1), {}, B.PT_EINVAL),                                         # not an earlier layer
         (skip(2, 0), {}, B.PT_EUNSUPPORTED),                                   # into the last layer
-        (skip(1, 0), dict(n_streams=32, w_dtype=B.PT_BF16), B.PT_EUNSUPPORTED),   # 32 streams: no skips
         (skip(1, 0, ps.mlp([8, 6, 8, 4], ps.ACT_RELU)), {}, B.PT_ESHAPE),      # sizes differ
     ]
     for layers, kw, code in cases:

@@ -435,6 +435,36 @@ def test_multistream_several_layers_per_stage_relu_mse_infer():
     p.close()
 
 
+@pytest.mark.parametrize("balance", [None, [6], [2, 2, 2], [1, 3, 2], [3, 1, 1, 1]])
+@pytest.mark.parametrize("adam", [None, (0.9, 0.999, 1e-8)])
+def test_multistream_skip_connections(balance, adam):
+    """Residual connections (Sec. V-C) on the 32-stream path: inside a stage, to the next stage and across several stages,
+    with a layer that is both the target of one skip and the source of another."""
+    w = ms_workload([97, 131, 131, 131, 131, 131, 11], ps.ACT_GELU, ps.LOSS_CE, lr=2e-3 if adam else 0.05, drift=0.05,
+                    seed=17, balance=balance)
+    for dst, src in {2: 0, 4: 1, 3: 2}.items():
+        w.layers[dst].skip_from = src
+    run_pair(w, 20, bf16=True, adam=adam)
+    run_pair(w, 20, bf16=True, adam=adam, pipes=[{}, {"chunks": [(0, 1), (1, 2), (2, 3), (3, 11), (11, 20)]}], k=0,
+             return_weights=True)
+
+
+def test_multistream_skip_connections_relu_mse_wide_and_infer():
+    w = ms_workload([200, 600, 600, 600, 260, 260, 7], ps.ACT_RELU, ps.LOSS_MSE, lr=0.02, drift=0.05, seed=18, balance=[2, 2, 2])
+    for dst, src in {2: 0, 4: 3}.items():
+        w.layers[dst].skip_from = src
+    run_pair(w, 16, bf16=True)
+    assert_sees_updates(w, 16, bf16=True)
+    Ws, bs = ps.init_weights(w.layers, w.seed)
+    x, _ = ps.make_inputs(w, 8)
+    ref = orc.Oracle(w.layers, Ws, bs, loss=w.loss, lr=w.lr, n_streams=32, w_bf16=True, operands_bf16=True, balance=w.balance)
+    p = Pipeline(w.layers, Ws, bs, loss=w.loss, lr=w.lr, n_streams=32, w_dtype=B.PT_BF16, balance=w.balance)
+    ro = ref.infer(x)
+    out = p.infer(torch.from_numpy(x).cuda()).cpu().numpy()
+    assert max(rel(out[t], ro[t]) for t in range(w.depth - 1, 8)) < BF16_TOL
+    p.close()
+
+
 def test_config4_full_size_multistream():
     """8 x 4096-wide bf16 layers (last 4096 -> 1000), 32 streams, at full size.  A tick of the plain-loop oracle is
     about 25 GFLOP here, so the pipeline is not filled tick by tick: it starts from a synthetic full state."""
