@@ -57,8 +57,8 @@ typedef struct {
   int c_in, c_out, h, w;
   int skip_from;       /* -1, or the index of an earlier layer whose output (same size) is added to this layer's
                           output after the activation (skip connections of Sec. V-C; the tensor and its gradient
-                          cross the stages in between one per tick, like the main path).  Dense layers of one stream
-                          or of 64 and more, and conv layers (equal channel counts); not PT_EXEC_PERSISTENT; one skip
+                          cross the stages in between one per tick, like the main path).  Dense layers (any stream
+                          count offered) and conv layers (equal channel counts); not PT_EXEC_PERSISTENT; one skip
                           per source layer; not into the last layer. */
 } pt_layer;
 
@@ -68,11 +68,11 @@ typedef struct {
   int depth;              /* D, number of pipeline stages (Eq. 3) */
   const int *balance;     /* host, depth entries: layers per stage (Eq. 3), sum = n_layers; NULL = one layer per stage.
                              Inside a stage back-propagation is exact (Eq. 5); only stage boundaries carry the delay.
-                             Several layers per stage: one stream or 64 and more, not PT_EXEC_PERSISTENT; dense layers, or conv
+                             Several layers per stage: not PT_EXEC_PERSISTENT; dense layers (any stream count offered), or conv
                              layers (one stream) with the pooled dense layer as a stage of its own. */
   int n_streams;          /* S independent streams sharing the weights; gradients and loss are means over S.
                              1, 32, or a multiple of 64 up to 1024 (the last: the slots of a replay batch, Sec. V-D);
-                             S > 1 takes dense layers and bf16 weights (S = 32 also one layer per stage) and rounds what
+                             S > 1 takes dense layers and bf16 weights and rounds what
                              enters a product to bf16 */
   int w_dtype;            /* PT_F32 / PT_BF16 */
   int loss;               /* PT_LOSS_* */
