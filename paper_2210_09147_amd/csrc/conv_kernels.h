@@ -125,10 +125,15 @@ __global__ __launch_bounds__(256, 2) void cv_conv_kernel(CvNet net, CvTick a) {
     // pooling for the head: mean of channel tl.a of what the last conv stage published one tick earlier
     const CvHead hd = net.head;
     const float *src = (prev ? hd.in_act[1] : hd.in_act[0]) + (size_t)tl.a * hd.hw;
+    // (eight requests at a time, at clamped addresses: one request per trip of a loop with a run-time bound is one memory
+    // round trip after the other)
     float s = 0.f;
-    for (int i = tid * 4; i < hd.hw; i += 1024) {
-      const float4 v = ldg_f4(src + i);
-      s += (v.x + v.y) + (v.z + v.w);
+    for (int i0 = tid * 4; i0 < hd.hw; i0 += 8 * 1024) {
+      float4 v[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) v[u] = ldg_f4(src + min(i0 + u * 1024, hd.hw - 4));
+#pragma unroll
+      for (int u = 0; u < 8; ++u) s += i0 + u * 1024 < hd.hw ? (v[u].x + v[u].y) + (v[u].z + v[u].w) : 0.f;
     }
     s = block_sum<4>(s, lds);
     if (tid == 0) stg_f(hd.gapv + tl.a, s / (float)hd.hw);
@@ -599,8 +604,18 @@ __global__ __launch_bounds__(256) void cv_update_kernel(CvNet net, int total, fl
         stg_f(sp->WBT + ((size_t)(ci / kCvCo) * (cop * 9) + co * 9 + (8 - tap)) * kCvCo + ci % kCvCo, w);
       } else {
         const int co = i - nw;
+        // (requested sixteen at a time like the weight partials: one request per trip would be n_ft memory round trips
+        // in a row, and these few threads set the length of the launch)
         float g = 0.f;
-        for (int p = 0; p < sp->n_ft; ++p) g += ldg_f(sp->dbp + (size_t)p * cop + co);
+        const int n_ft = sp->n_ft;
+        const float *dp = sp->dbp + co;
+        for (int p = 0; p < n_ft; p += 16) {
+          float v[16];
+#pragma unroll
+          for (int u = 0; u < 16; ++u) v[u] = ldg_f(dp + (size_t)min(p + u, n_ft - 1) * cop);
+#pragma unroll
+          for (int u = 0; u < 16; ++u) g += p + u < n_ft ? v[u] : 0.f;
+        }
         stg_f(sp->b + co, cv_step(net, adam_c1, adam_c2, ldg_f(sp->b + co), g, sp->mb, sp->vb, co));
       }
       return;

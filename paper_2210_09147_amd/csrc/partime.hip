@@ -1935,7 +1935,12 @@ int init_conv(partime_ctx *c, const float *const *w_host, const float *const *b_
         for (int ob = 0; ob < v.co_pad / kCvCo; ++ob) tw.push_back(CvTile{h, band, ib, ob});
     c->cv_total_w += v.co_pad * v.c_in * 9 + v.co_pad;
   }
-  for (int ch = 0; ch < c_last; ++ch) tf[0].push_back(CvTile{0, ch, 0, 1});
+  {
+    // the pooling tiles go first: they are short, and behind the conv tiles they would start a round of their own
+    std::vector<CvTile> pool;
+    for (int ch = 0; ch < c_last; ++ch) pool.push_back(CvTile{0, ch, 0, 1});
+    tf[0].insert(tf[0].begin(), pool.begin(), pool.end());
+  }
   tb[0].insert(tb[0].begin(), CvTile{0, 0, 0, 2});   // the head first: an inference tick launches that tile alone
   std::vector<CvTile> all;
   c->cv_f_off.clear(); c->cv_f_cnt.clear(); c->cv_b_off.clear(); c->cv_b_cnt.clear();
