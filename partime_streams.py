@@ -173,6 +173,11 @@ def workload(cfg: int, ticks: Optional[int] = None) -> Workload:
         for dst in (2, 4, 6):
             w.layers[dst].skip_from = dst - 2
         w.name += "_skips"
+    elif cfg == 21:
+        # workload 4 as four stages of two layers
+        w = workload(4)
+        w.balance = [2, 2, 2, 2]
+        w.name += "_d4"
     else:
         raise ValueError(cfg)
     if ticks is not None:

@@ -472,6 +472,13 @@ def test_config4_full_size_multistream():
     full_size_forced(w, w.depth + 1, bf16=True, synthetic=True, rel_step=0.1)
 
 
+def test_config4_full_size_multistream_two_layers_per_stage():
+    """The same network as four stages of two layers (Eq. 3-5), at full size, from a synthetic full pipeline: forward-only
+    matrix launches, kept pre-activations and in-stage deltas at 4096-wide layers."""
+    w = ps.workload(21)
+    full_size_forced(w, w.depth + 1, bf16=True, synthetic=True, rel_step=0.1)
+
+
 # ----------------------------------------------------------------------------- replay batch: 64 and more streams
 
 def batched_workload(widths, act, loss, S, **kw):
