@@ -898,8 +898,8 @@ def test_conv_frames_256_wide(feat, h, act, adam):
 
 def test_bandwidth_probe_returns_a_plausible_rate():
     for mode in (0, 1, 2):
-        g = B.partime_bandwidth_probe(64 << 20, mode, 5)
-        assert 200.0 < g < 40000.0, (mode, g)          # GB/s; far below any cache-resident rate, far above a stall
+        g = B.partime_bandwidth_probe(512 << 20, mode, 5)   # twice the memory-side cache: the rate is HBM's
+        assert 2000.0 < g < 8000.0, (mode, g)               # GB/s: under the published peak, not a stall
     with pytest.raises(B.PartimeError):
         B.partime_bandwidth_probe(1024, 0, 5)          # below the minimum size
 
