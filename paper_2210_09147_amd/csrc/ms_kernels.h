@@ -11,13 +11,14 @@
 //   ms_vec_kernel   (vectors only)  z(t) = b + sum of the partial planes the previous matrix launch left (Eq. 6),
 //                   o = phi(z), published in fp32 and as bf16 in both orientations; g = the error the next stage
 //                   published one tick earlier (sum of its planes, Eq. 11), delta = rnd(g * phi'(z)) (Eq. 9) in both
-//                   orientations, bias update; rnd(x(t)) transposed and rnd(x(t+1)) for the first stage
-//   ms_mat_kernel   tile = up to 512 rows x 512 columns of one stage's W, one pass: E = W^T delta with the old W
+//                   orientations, bias update; the last stage's softmax statistics per 64 rows; rnd(x(t)) transposed and
+//                   rnd(x(t+1)) for the first stage
+//   ms_mat_kernel   tile = a block of rows x 512 columns of one stage's W, one pass: E = W^T delta with the old W
 //                   (error plane of this row tile), W <- rnd(W - eta/S * delta rnd(x)^T)  (Algorithm 1, last two
 //                   steps), then Z(t+1) partial = W_new * rnd(x(t+1)) over the tile's columns (plane of this column
-//                   tile).  Its first work-group runs the loss head of the last stage (softmax / squared error over all
-//                   outputs, delta, bias); the tiles of the last stage, which come last in the launch, start once that
-//                   work-group has raised its flag.
+//                   tile).  Its first work-groups are the loss head of the last stage, 64 rows each (softmax / squared
+//                   error, delta, bias); the tiles of the last stage, which come last in the launch, start once all
+//                   of them have counted themselves in.
 // x(t+1) of a stage is what the stage in front of it has just published, and for the first stage the caller's next
 // sample; at the last tick of a call that sample is not known yet, so the first stage's planes are formed by a
 // forward-only launch of the same kernel over that stage when the next call begins.  The same forward-only mode
