@@ -230,6 +230,37 @@ def test_adam_first_step_has_the_closed_form():
     np.testing.assert_allclose(vW, (1 - b2) * np.array([[-1.75, -3.5]]) ** 2, rtol=1e-6)
 
 
+def test_adam_counts_the_fill_ticks_of_every_stage_as_steps():
+    """Two scalar stages (identity, w = 1, x = 1, target 0, squared error): the last stage sees its first gradient
+    (2) at tick 1, the first stage (through the error published then) at tick 2; the ticks before carry a zero gradient
+    but count as optimiser steps, so the bias corrections of those first real steps are those of step 2 and step 3.
+    torch.optim.Adam, stepped with the same gradient sequences, must land on the same weights."""
+    layers = [ps.LayerSpec(ps.DENSE, ps.ACT_ID, 1, 1), ps.LayerSpec(ps.DENSE, ps.ACT_ID, 1, 1)]
+    one, zero = np.ones((1, 1), dtype=np.float32), np.zeros(1, dtype=np.float32)
+    lr, betas, eps = 0.01, (0.9, 0.999), 1e-8
+    x, tg = np.ones((3, 1, 1), dtype=np.float32), np.zeros((3, 1, 1), dtype=np.float32)
+
+    def torch_walk(grads):
+        q = torch.ones(1, dtype=torch.float64, requires_grad=True)
+        opt = torch.optim.Adam([q], lr=float(np.float32(lr)), betas=tuple(float(np.float32(v)) for v in betas),
+                               eps=float(np.float32(eps)))
+        for g in grads:
+            q.grad = torch.full_like(q, g)
+            opt.step()
+        return q.item()
+
+    o = orc.Oracle(layers, [one.copy(), one.copy()], [zero.copy(), zero.copy()], loss=ps.LOSS_MSE, lr=lr, target_delay=0,
+                   adam=(*betas, eps))
+    o.step(x[:2], tg[:2])
+    assert o.get_weights(0)[0][0, 0] == 1.0                       # no gradient has reached the first stage yet
+    w2 = o.get_weights(1)[0][0, 0]
+    np.testing.assert_allclose(w2, torch_walk([0.0, 2.0]), rtol=1e-6)
+    # (had the fill tick not counted, the first real step would be a full lr)
+    assert abs((1.0 - w2) / lr - 1.0) > 0.2
+    o.step(x[2:], tg[2:])
+    np.testing.assert_allclose(o.get_weights(0)[0][0, 0], torch_walk([0.0, 0.0, 2.0]), rtol=1e-6)
+
+
 # ----------------------------------------------------------------------------- Eq. 9 at steady state
 
 @pytest.mark.parametrize("loss", [ps.LOSS_MSE, ps.LOSS_CE])
