@@ -153,10 +153,6 @@ __device__ __forceinline__ uint2 ldg8(const void *p) { const pt_v2u t = *(const 
 __device__ __forceinline__ void stg8(void *p, const uint2 &v) { const pt_v2u t = {v.x, v.y}; *(g_v2u *)p = t; }
 __device__ __forceinline__ float4 ldg_f4(const void *p) { const pt_v4f t = *(const g_v4f *)p; return make_float4(t.x, t.y, t.z, t.w); }
 __device__ __forceinline__ void stg_f4(void *p, const float4 &v) { const pt_v4f t = {v.x, v.y, v.z, v.w}; *(g_v4f *)p = t; }
-// streaming variants: what is written once and read once a whole launch later (partial-sum planes) is kept out of the
-// memory-side cache, which is better spent on the weights
-__device__ __forceinline__ float4 ldg_f4_stream(const void *p) { const pt_v4f t = __builtin_nontemporal_load((const g_v4f *)p); return make_float4(t.x, t.y, t.z, t.w); }
-__device__ __forceinline__ void stg_f4_stream(void *p, const float4 &v) { const pt_v4f t = {v.x, v.y, v.z, v.w}; __builtin_nontemporal_store(t, (g_v4f *)p); }
 __device__ __forceinline__ float ldg_f(const void *p) { return *(const g_f32 *)p; }
 __device__ __forceinline__ void stg_f(void *p, float v) { *(g_f32 *)p = v; }
 __device__ __forceinline__ int ldg_i(const void *p) { return *(const g_i32 *)p; }
