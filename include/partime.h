@@ -146,7 +146,13 @@ int partime_set_state(partime_ctx *ctx, int layer, const float *w_host, const fl
  *              against (text under Eq. 10 with the pairing of Eq. 7): target_delay x one tick's targets, copied as
  *              the 4-byte elements they were supplied in (fp32, or int32 class ids behind the float pointer);
  *              stage and half are ignored; nothing is copied when target_delay = 0
- *   half  = 0/1: the half written at even / odd ticks.
+ *   which = 3 / 4: the delay lines of the skip connection that ends in layer `stage` (a layer index here): 3 = the
+ *              skipped tensor on its way forward, 4 = the gradient on its way back, each [S][layer out size]
+ *              (conv: [C][H][W]); `half` is the AGE of the entry in ticks, 0 = written during the last tick ...
+ *              d - 1 = the one the coming tick consumes (d = stage boundaries the skip crosses; a skip inside a stage
+ *              has nothing in flight between ticks).  Ages count back from the tick counter: use after
+ *              partime_set_tick, and not across inference ticks (those move the tensors, not the gradients).
+ *   half  = 0/1 (which < 2): the half written at even / odd ticks.
  * Pipelines of 64 and more streams keep activations rounded to bf16: those come back, and are taken, as such.
  */
 int partime_get_buffer(partime_ctx *ctx, int which, int stage, int half, float *host);

@@ -51,6 +51,8 @@ def _load():
         lib.oracle_get_grads.argtypes = [vp, ctypes.c_int, dp, dp]
         lib.oracle_get_buffer.argtypes = [vp, ctypes.c_int, ctypes.c_int, ctypes.c_int, fp]
         lib.oracle_set_buffer.argtypes = [vp, ctypes.c_int, ctypes.c_int, ctypes.c_int, fp]
+        lib.oracle_lane.restype = ctypes.c_int
+        lib.oracle_lane.argtypes = [vp, ctypes.c_int, ctypes.c_int, ctypes.c_int, fp, ctypes.c_int]
         lib.oracle_get_history.argtypes = [vp, vp]
         lib.oracle_set_history.argtypes = [vp, vp]
         lib.oracle_get_tick.restype = ctypes.c_long
@@ -193,6 +195,24 @@ class Oracle:
         n = self.stage_out[stage] if which == "act" else self.stage_in[stage]
         a = np.ascontiguousarray(a, dtype=np.float32).reshape(self.S, n)
         self.lib.oracle_set_buffer(self.h, 0 if which == "act" else 1, stage, half, _fp(a))
+
+    def skip_delay(self, layer):
+        """Stage boundaries the skip into `layer` crosses (0: none, or no skip)."""
+        src = self.layers[layer].skip_from
+        if src < 0:
+            return 0
+        stage_of = [h for h, c in enumerate(self.balance) for _ in range(c)]
+        return stage_of[layer] - stage_of[src]
+
+    def get_lane(self, kind, layer, age):
+        """Delay line of the skip into `layer`: kind 0 the skipped tensor, 1 its gradient; age 0 = written in the last tick."""
+        a = np.empty((self.S, self.layers[layer].out_size), dtype=np.float32)
+        assert self.lib.oracle_lane(self.h, layer, kind, age, _fp(a), 0) == 0
+        return a
+
+    def set_lane(self, kind, layer, age, a):
+        a = np.ascontiguousarray(a, dtype=np.float32).reshape(self.S, self.layers[layer].out_size)
+        assert self.lib.oracle_lane(self.h, layer, kind, age, _fp(a), 1) == 0
 
     def get_history(self):
         """The targets of the last target_delay ticks, oldest first, as raw 4-byte elements (float32 view)."""

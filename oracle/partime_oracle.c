@@ -517,6 +517,22 @@ void oracle_set_buffer(void *p, int which, int stage, int half, const float *src
   long sz = (long)n->S * (which == 0 ? stage_out(n, stage) : stage_in(n, stage));
   memcpy(which == 0 ? n->act[half][stage] : n->err[half][stage], src, sz * sizeof(float));
 }
+/* Test access to the delay lines of the skip that ends in layer `layer`: kind 0 = the skipped tensor, 1 = the gradient
+ * on its way back; age 0 = the entry written during the last tick, age d - 1 (d = stage boundaries crossed) the one
+ * the coming tick consumes.  set != 0 writes, else reads; [S][out_size].  Returns 0, or -1 if there is no such entry. */
+int oracle_lane(void *p, int layer, int kind, int age, float *buf, int set) {
+  net_t *n = (net_t *)p;
+  if (layer < 0 || layer >= n->n_layers || n->layers[layer].skip_src < 0) return -1;
+  layer_t *l = &n->layers[layer];
+  const int hs = n->stage_of[l->skip_src], ht = n->stage_of[layer];
+  if (age < 0 || age >= ht - hs) return -1;
+  const int half = (int)((n->tick + 1) & 1);   /* the half the last tick wrote */
+  float *lane = kind == 0 ? l->lane_a[half][hs + age] : l->lane_e[half][ht - age];
+  const size_t bytes = (size_t)n->S * l->out_size * sizeof(float);
+  if (set) memcpy(lane, buf, bytes);
+  else memcpy(buf, lane, bytes);
+  return 0;
+}
 /* the targets of the last k ticks, oldest first (k x one tick's targets, 4-byte elements) */
 void oracle_get_history(void *p, void *dst) {
   net_t *n = (net_t *)p;

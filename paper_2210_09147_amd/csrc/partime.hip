@@ -2738,10 +2738,46 @@ int partime_set_state(partime_ctx *ctx, int layer, const float *w_host, const fl
 static int buffer_args(partime_ctx *ctx, int which, int stage, int half, const void *host, const char *fn) {
   if (!ctx || !host) return fail(PT_EINVAL, "%s: null argument", fn);
   if (which == 2) return PT_OK;   // the target history: stage and half are not used
-  if (which < 0 || which > 1 || half < 0 || half > 1 || stage < 0 || stage >= ctx->depth)
+  if (which == 3 || which == 4) return PT_OK;   // delay lines of a skip connection: checked by ring_slot
+  if (which < 0 || which > 4 || half < 0 || half > 1 || stage < 0 || stage >= ctx->depth)
     return fail(PT_EINVAL, "%s: which/stage/half out of range", fn);
   if (which == 0 && stage == ctx->depth - 1) return fail(PT_EINVAL, "%s: the last stage publishes no activation", fn);
   if (which == 1 && stage == 0) return fail(PT_EINVAL, "%s: the first stage publishes no error", fn);
+  return PT_OK;
+}
+
+// Delay lines of the skip connection that ends in layer `layer` (which = 3: the skipped tensor, 4: the gradient that
+// travels back): where the entry written `age` ticks before the coming tick's predecessor sits (age 0 = written during
+// the last tick), how many streams and values per stream it has and how far apart the streams are in memory.
+struct RingSlot {
+  float *p;
+  int S, n, pitch;
+};
+static int ring_slot(partime_ctx *ctx, int which, int layer, int age, const char *fn, RingSlot *out) {
+  if (layer < 0 || layer >= (int)ctx->layers.size() || ctx->layers[layer].skip_from < 0)
+    return fail(PT_EINVAL, "%s: layer %d is not the target of a skip connection", fn, layer);
+  float *ring = nullptr;
+  int d = 0;
+  size_t slot = 0;
+  if (ctx->cv) {
+    CvStageHost &v = ctx->cvs[layer];
+    ring = which == 3 ? v.skip_ring : v.serr_ring;
+    d = v.skip_delay;
+    slot = (size_t)v.co_pad * v.H * v.W;
+    out->S = 1; out->n = v.c_out * v.H * v.W; out->pitch = out->n;   // the real channels come first
+  } else {
+    StageHost &s = ctx->stages[layer];
+    ring = which == 3 ? s.skip_ring : s.serr_ring;
+    d = s.skip_delay;
+    const bool padded = ctx->ms || ctx->rb;
+    out->S = ctx->S; out->n = s.out_dim; out->pitch = padded ? s.out_pad : s.out_dim;
+    slot = (size_t)ctx->S * out->pitch;
+  }
+  if (age < 0 || age >= d)
+    return fail(PT_EINVAL, "%s: the skip into layer %d crosses %d stage boundaries: ages 0 .. %d", fn, layer, d, d - 1);
+  // slot of tick t = t mod (d + 1), as in the kernels (before tick 0 nothing was written: those slots hold their zeros)
+  const int64_t n = d + 1, t = ctx->tick - 1 - age;
+  out->p = ring + (size_t)(((t % n) + n) % n) * slot;
   return PT_OK;
 }
 
@@ -2749,6 +2785,12 @@ int partime_get_buffer(partime_ctx *ctx, int which, int stage, int half, float *
   int rc = buffer_args(ctx, which, stage, half, host, "partime_get_buffer");
   if (rc != PT_OK) return rc;
   if ((rc = sync_and_check(ctx)) != PT_OK) return rc;
+  if (which == 3 || which == 4) {
+    RingSlot r;
+    if ((rc = ring_slot(ctx, which, stage, half, "partime_get_buffer", &r)) != PT_OK) return rc;
+    HIP_TRY(hipMemcpy2D(host, (size_t)r.n * 4, r.p, (size_t)r.pitch * 4, (size_t)r.n * 4, r.S, hipMemcpyDeviceToHost));
+    return PT_OK;
+  }
   if (which == 2) {
     // the last target_delay targets, oldest first, as the 4-byte elements the caller supplied them in
     if (ctx->k > 0 && ctx->cfg.loss != PT_LOSS_NONE)
@@ -2828,6 +2870,12 @@ int partime_set_buffer(partime_ctx *ctx, int which, int stage, int half, const f
   if (rc != PT_OK) return rc;
   HIP_TRY(hipStreamSynchronize(ctx->stream));
   ctx->ms_zp_valid = false;
+  if (which == 3 || which == 4) {
+    RingSlot r;
+    if ((rc = ring_slot(ctx, which, stage, half, "partime_set_buffer", &r)) != PT_OK) return rc;
+    HIP_TRY(hipMemcpy2D(r.p, (size_t)r.pitch * 4, host, (size_t)r.n * 4, (size_t)r.n * 4, r.S, hipMemcpyHostToDevice));
+    return PT_OK;
+  }
   if (which == 2) {
     if (ctx->k > 0 && ctx->cfg.loss != PT_LOSS_NONE)
       HIP_TRY(hipMemcpy(ctx->d_hist[ctx->hist_cur], host, (size_t)ctx->k * ctx->tgt_bytes, hipMemcpyHostToDevice));

@@ -208,6 +208,11 @@ class Pair:
             if self.k > 0:
                 B.partime_set_buffer(p.ctx, 2, 0, 0, src.get_history())
             B.partime_set_tick(p.ctx, src.tick)
+            # the delay lines of skip connections, by age (the library keeps them in rings indexed by the tick: after set_tick)
+            for i in range(len(self.layers)):
+                for age in range(src.skip_delay(i)):
+                    B.partime_set_buffer(p.ctx, 3, i, age, src.get_lane(0, i, age))
+                    B.partime_set_buffer(p.ctx, 4, i, age, src.get_lane(1, i, age))
         self.sync = st
         self.sync_tick = src.tick
 
@@ -281,6 +286,17 @@ class Pair:
                     assert h < self.D - 1 or float(np.abs(want).max()) > 1e-6 or ref.tick <= max(self.D - 1, self.k), \
                         f"the loss gradient has collapsed (error of the last stage {float(np.abs(want).max()):.1e}): choose inputs that keep the loss up"
                     compare(rep, f"{nm} err{h}", got, want, tol, P=Pe, N=Ne)
+            # what the last tick put into the delay lines of skip connections that cross stage boundaries
+            for i in range(len(self.layers)):
+                if ref.skip_delay(i) < 1:
+                    continue
+                want = ref.get_lane(0, i, 0)
+                compare(rep, f"{nm} skipped tensor into layer {i}", B.partime_get_buffer(p.ctx, 3, i, 0, want.size), want, tol)
+                want = ref.get_lane(1, i, 0)
+                Pe = Ne = None
+                if P is not None:
+                    Pe, Ne = P.get_lane(1, i, 0), N.get_lane(1, i, 0)
+                compare(rep, f"{nm} skip gradient of layer {i}", B.partime_get_buffer(p.ctx, 4, i, 0, want.size), want, tol, P=Pe, N=Ne)
 
     def _check_outputs(self, outs, losses, a, b):
         for pi in range(len(self.pipes)):

@@ -43,7 +43,6 @@ def run_pair(w, T, chunks=None, bf16=False, tol=None, k=None, exec_mode=B.PT_EXE
     updates, moments and published buffers are compared (see parity.py).  min_move: every layer must have moved by at
     least this fraction of its largest weight, so that the update check cannot pass on weights that never change."""
     pipes = pipes or [{"exec_mode": exec_mode, "chunks": chunks}]
-    has_skips = any(getattr(l, "skip_from", -1) >= 0 for l in w.layers)
     if x is not None:
         assert len(x) == T + 1
     pair = Pair(w, bf16=bf16, k=k, adam=adam, tol=tol, pipes=pipes, T=T + 1, x=x, tg=tg)
@@ -54,15 +53,12 @@ def run_pair(w, T, chunks=None, bf16=False, tol=None, k=None, exec_mode=B.PT_EXE
         assert np.all(l[:fill] == 0)
     if expect_blind:
         return pair
-    if not has_skips:
-        # one more tick, taken from the oracle's state on both sides: everything at the full bar.  (Not for nets with
-        # skip connections: the delay lines of the skipped tensors cannot be handed over through the C ABI.)
-        # negative: under a step size that lifts every layer's update well above the storage rounding of its weights,
-        # and first with a library that does not update at all, which must fail for every layer
-        big = 0.1 if (bf16 or w.n_streams > 1) else 0.02
-        pair.forced_tick(T, lr=pair.pick_lr(big) if negative else None, negative=negative)
-    else:
-        assert not negative, "use assert_sees_updates for nets with skip connections"
+    # one more tick, taken from the oracle's state on both sides (weights, moments, buffers, target history, the delay
+    # lines of skip connections, tick): everything at the full bar.
+    # negative: under a step size that lifts every layer's update well above the storage rounding of its weights,
+    # and first with a library that does not update at all, which must fail for every layer
+    big = 0.1 if (bf16 or w.n_streams > 1) else 0.02
+    pair.forced_tick(T, lr=pair.pick_lr(big) if negative else None, negative=negative)
     pair.assert_ok()
     if min_move is not None:
         mv = movement(pair)
@@ -444,7 +440,7 @@ def test_multistream_skip_connections(balance, adam):
                     seed=17, balance=balance)
     for dst, src in {2: 0, 4: 1, 3: 2}.items():
         w.layers[dst].skip_from = src
-    run_pair(w, 20, bf16=True, adam=adam)
+    run_pair(w, 20, bf16=True, adam=adam, negative=True)
     run_pair(w, 20, bf16=True, adam=adam, pipes=[{}, {"chunks": [(0, 1), (1, 2), (2, 3), (3, 11), (11, 20)]}], k=0,
              return_weights=True)
 
@@ -571,7 +567,7 @@ def test_batched_skip_connections(balance, adam):
                          seed=17, balance=balance)
     for dst, src in {2: 0, 4: 1, 3: 2}.items():
         w.layers[dst].skip_from = src
-    run_pair(w, 20, bf16=True, adam=adam)
+    run_pair(w, 20, bf16=True, adam=adam, negative=True)
     run_pair(w, 20, bf16=True, adam=adam, chunks=[(0, 1), (1, 2), (2, 3), (3, 11), (11, 20)], k=0)
 
 
@@ -920,7 +916,7 @@ def test_skip_connections_fp32(balance, loss):
     gradient wait in delay lines as long as the stages they cross."""
     w = skip_workload([97, 131, 131, 131, 131, 131, 11], {2: 0, 4: 1, 3: 2}, ps.ACT_GELU, loss, lr=0.02, drift=0.05,
                       seed=41, balance=balance)
-    run_pair(w, 40, min_move=1e-3)
+    run_pair(w, 40, min_move=1e-3, negative=True)
     run_pair(w, 40, chunks=[(0, 1), (1, 2), (2, 3), (3, 21), (21, 40)], k=0)
     if balance == [1, 3, 2] and loss == ps.LOSS_MSE:
         assert_sees_updates(w, 16)
@@ -978,6 +974,31 @@ def test_inference_bf16_between_learning_calls():
     p.close()
 
 
+def test_skip_delay_lines_through_get_and_set_buffer():
+    """The delay lines of a skip that crosses stage boundaries are part of what a pipeline carries from tick to tick:
+    read by age, written back, refused for layers without a skip and for ages that are not in flight."""
+    w = ps.small_mlp([40, 48, 48, 48, 48, 6], ps.ACT_GELU, ps.LOSS_MSE, lr=0.05, drift=0.05, seed=33)
+    w.layers[3].skip_from = 0                                  # three boundaries
+    Ws, bs = ps.init_weights(w.layers, w.seed)
+    x, tg = ps.make_inputs(w, 12)
+    ref = orc.Oracle(w.layers, Ws, bs, loss=w.loss, lr=w.lr, target_delay=w.k)
+    p = Pipeline(w.layers, Ws, bs, loss=w.loss, lr=w.lr, target_delay=w.k)
+    ref.step(x[:9], tg[:9])
+    p.step(torch.from_numpy(x[:9]).cuda(), torch.from_numpy(tg[:9]).cuda())
+    for age in range(3):
+        for which in (3, 4):
+            want = ref.get_lane(which - 3, 3, age)
+            got = B.partime_get_buffer(p.ctx, which, 3, age, want.size)
+            assert rel(got, want) < 1e-4, (which, age, rel(got, want))
+            B.partime_set_buffer(p.ctx, which, 3, age, want)
+            assert np.array_equal(B.partime_get_buffer(p.ctx, which, 3, age, want.size), want.ravel())
+    for layer, age in ((2, 0), (3, 3), (3, -1)):
+        with pytest.raises(B.PartimeError) as e:
+            B.partime_get_buffer(p.ctx, 3, layer, age, 48)
+        assert e.value.code == B.PT_EINVAL
+    p.close()
+
+
 def test_skip_connections_wide_full_rows():
     w = skip_workload([4096, 4096, 4096, 4096, 64], {2: 0}, ps.ACT_GELU, ps.LOSS_MSE, lr=0.02, drift=0.01, seed=43)
     run_pair(w, 12, min_move=1e-3)
@@ -1000,7 +1021,7 @@ def test_conv_skip_connections(balance, loss):
     The skipped map and its gradient wait in rings of frames as long as the stages they cross.  37 channels: the last
     channel block is ragged."""
     wl = conv_skip_workload(16, 32, 6, 37, {2: 0, 4: 1, 3: 2}, loss=loss, lr=0.05, seed=71, balance=balance)
-    run_pair(wl, 24, tol=CONV_TOL, min_move=1e-4)
+    run_pair(wl, 24, tol=CONV_TOL, min_move=1e-4, negative=True)
     if loss == ps.LOSS_CE:
         run_pair(wl, 24, tol=CONV_TOL, chunks=[(0, 1), (1, 2), (2, 3), (3, 13), (13, 24)], k=0)
     if balance == [1, 3, 2, 1] and loss == ps.LOSS_MSE:

@@ -261,6 +261,30 @@ def test_adam_counts_the_fill_ticks_of_every_stage_as_steps():
     np.testing.assert_allclose(o.get_weights(0)[0][0, 0], torch_walk([0.0, 0.0, 2.0]), rtol=1e-6)
 
 
+def test_delay_lines_of_a_skip_by_age():
+    """Test access to the delay lines: with frozen weights the entry of age j of the skipped tensor is the source layer's
+    output for the sample that entered the pipeline j ticks before the last one (Eq. 7 at the source's stage), computed
+    here with torch; an entry written and read back is unchanged and ages by one per tick."""
+    widths, S = [5, 6, 6, 6, 6, 3], 2
+    layers = ps.mlp(widths, ps.ACT_GELU)
+    layers[3].skip_from = 0                                   # crosses three stage boundaries
+    Ws, bs = ps.init_weights(layers, 31)
+    o = orc.Oracle(layers, Ws, bs, n_streams=S, loss=ps.LOSS_MSE, lr=0.0)
+    assert [o.skip_delay(i) for i in range(5)] == [0, 0, 0, 3, 0]
+    T = 7
+    x = rand_stream(T, S, 5, 3)
+    o.step(x, targets_for(ps.LOSS_MSE, T, S, 3, 3))
+    for age in range(3):
+        # the source is layer 0 = stage 0: its output at tick t belongs to the sample of tick t
+        want = torch.nn.functional.gelu(t64(x[T - 1 - age]) @ t64(Ws[0]).T + t64(bs[0])).numpy()
+        np.testing.assert_allclose(o.get_lane(0, 3, age), want, rtol=1e-6, atol=1e-7)
+    a1 = o.get_lane(0, 3, 1)
+    o.set_lane(0, 3, 1, a1 * 2)
+    assert np.array_equal(o.get_lane(0, 3, 1), a1 * 2)
+    o.step(x[:1], targets_for(ps.LOSS_MSE, 1, S, 3, 4))
+    assert np.array_equal(o.get_lane(0, 3, 2), a1 * 2)
+
+
 # ----------------------------------------------------------------------------- Eq. 9 at steady state
 
 @pytest.mark.parametrize("loss", [ps.LOSS_MSE, ps.LOSS_CE])
