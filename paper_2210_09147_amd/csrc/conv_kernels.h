@@ -117,7 +117,9 @@ __device__ __forceinline__ f32x16_t mfma32(float a, float b, f32x16_t c) {
 // ------------------------------------------------------------------------------------------------
 template <int MODE, bool LEARN, int LW>
 __global__ __launch_bounds__(256, 2) void cv_conv_kernel(CvNet net, CvTick a) {
-  extern __shared__ float lds[];
+  // (aligned: behind a static LDS variable of the kernel the array would otherwise start at an odd word, and every 16-byte
+  // access to it would be a misaligned one: the 8 x 4096 fp32 workload ran 8 % slower that way)
+  extern __shared__ __attribute__((aligned(16))) float lds[];
   const CvTile tl = MODE == CV_FWD ? net.tiles_f[blockIdx.x] : net.tiles_b[blockIdx.x];
   const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6, prev = a.cur ^ 1;
 
@@ -458,7 +460,9 @@ __device__ __forceinline__ f32x4_t mfma16f(float a, float b, f32x4_t c) {
 
 template <int XC>
 __global__ __launch_bounds__(512) void cv_wgrad_kernel(CvNet net, CvTick a) {
-  extern __shared__ float lds[];
+  // (aligned: behind a static LDS variable of the kernel the array would otherwise start at an odd word, and every 16-byte
+  // access to it would be a misaligned one: the 8 x 4096 fp32 workload ran 8 % slower that way)
+  extern __shared__ __attribute__((aligned(16))) float lds[];
   constexpr int kPitch = XC + 12, XC4 = XC / 4;             // pixel x of a staged row at index x - xc0 + 4
   constexpr int kSlot = kCvWgCi * kPitch, NQ = (kCvWgCi * XC4 + 63) / 64;
   const CvTile tl = net.tiles_w[blockIdx.x];
