@@ -316,6 +316,13 @@ def test_multistream_small_ragged(loss):
     run_pair(w, 20, bf16=True, min_move=2e-2)
 
 
+def test_multistream_hidden_layer_wider_than_4096():
+    """A hidden layer of 4200 units (padded to 4608): nine row tiles and nine column tiles, so every sum over partial planes
+    runs past its first batch of requests and ends in a clamped, masked tail."""
+    w = ms_workload([64, 4200, 40], ps.ACT_GELU, ps.LOSS_CE, lr=0.05, drift=0.05, seed=41)
+    run_pair(w, 8, bf16=True, negative=True)
+
+
 def test_multistream_depth8_medium():
     w = ms_workload([512] * 8 + [100], ps.ACT_RELU, ps.LOSS_CE, lr=0.01, drift=0.02, seed=5)
     pair = Pair(w, T=28)
