@@ -981,6 +981,38 @@ def test_inference_bf16_between_learning_calls():
     p.close()
 
 
+def test_calls_of_zero_ticks_change_nothing():
+    """Empty input: a learning or inference call of zero ticks is accepted and leaves every kernel family's pipeline where
+    it was; the run around it is bit for bit the uninterrupted one."""
+    cases = [
+        (ps.small_mlp([40, 48, 32, 6], ps.ACT_RELU, ps.LOSS_CE, lr=0.05, drift=0.05, seed=51), {}),
+        (ms_workload([40, 48, 32, 6], ps.ACT_RELU, ps.LOSS_CE, lr=0.05, drift=0.05, seed=52), dict(n_streams=32, w_dtype=B.PT_BF16)),
+        (batched_workload([40, 48, 32, 6], ps.ACT_RELU, ps.LOSS_CE, 64, lr=0.05, drift=0.05, seed=53), dict(n_streams=64, w_dtype=B.PT_BF16)),
+        (conv_workload(3, 32, 32, 2, 5, lr=0.05, seed=54), {}),
+    ]
+    for w, kw in cases:
+        Ws, bs = ps.init_weights(w.layers, w.seed)
+        x, tg = ps.make_inputs(w, 10)
+        xd, td = torch.from_numpy(x).cuda(), torch.from_numpy(tg).cuda()
+        outs = []
+        for split in (False, True):
+            p = Pipeline(w.layers, Ws, bs, loss=w.loss, lr=w.lr, target_delay=w.k, **kw)
+            if split:
+                o1, l1 = p.step(xd[:4], td[:4])
+                o0, l0 = p.step(xd[4:4], td[4:4])
+                assert o0.shape[0] == 0 and l0.shape[0] == 0 and p.infer(xd[:0]).shape[0] == 0
+                o2, l2 = p.step(xd[4:], td[4:])
+                o, l = torch.cat([o1, o2]), torch.cat([l1, l2])
+            else:
+                o, l = p.step(xd, td)
+            outs.append((o.cpu().numpy(), l.cpu().numpy(), [p.weights(i)[0] for i in range(len(w.layers))]))
+            B.partime_sync(p.ctx)
+            p.close()
+        assert np.array_equal(outs[0][0], outs[1][0]) and np.array_equal(outs[0][1], outs[1][1]), w.name
+        for W0, W1 in zip(outs[0][2], outs[1][2]):
+            assert np.array_equal(W0, W1), w.name
+
+
 def test_skip_delay_lines_through_get_and_set_buffer():
     """The delay lines of a skip that crosses stage boundaries are part of what a pipeline carries from tick to tick:
     read by age, written back, refused for layers without a skip and for ages that are not in flight."""
