@@ -167,10 +167,17 @@ struct MsTile {
                              // matrix kernel: kind 0: a = row tile, b = column tile; kind 2: loss head, rows [a, a + 64)
 };
 
+// What a work-group reads first: its tile and, in the same record, a copy of the layer's record.  With the layer records
+// in an array of their own a work-group would read the tile, then the layer, then its data: three memory round trips
+// in a row at the start of every launch, each of them cold.
+struct MsTileRec {
+  MsTile t;
+  MsStage s;
+};
+
 struct MsNet {
-  const MsStage *stages;
-  const MsTile *tiles_v, *tiles_m, *tiles_f;   // vector launch; matrix launch of a learning tick; forward-only matrix launch
-  const MsTile *tiles_i;                       // inference launch (tile: a = first of 64 rows)
+  const MsTileRec *tiles_v, *tiles_m, *tiles_f;   // vector launch; matrix launch of a learning tick; forward-only matrix launch
+  const MsTileRec *tiles_i;                       // inference launch (tile: a = first of 64 rows)
   int loss, out_dim, adam;
   float lr_over_s, inv_s, beta1, beta2, eps;
   unsigned int *head_flag;  // number of head tiles that have finished since the counter was last cleared
@@ -246,8 +253,9 @@ __device__ __forceinline__ void ms_add_planes(const float *p0, int n, size_t pla
 template <bool LEARN>
 __global__ __launch_bounds__(256) void ms_vec_kernel(MsNet net, MsTick a) {
   __shared__ __attribute__((aligned(16))) unsigned short tr[2][kMsVR * kMsS];   // bf16 [row][stream]: outputs, deltas
-  const MsTile tl = net.tiles_v[blockIdx.x];
-  const MsView st = ms_view(net.stages + tl.stage, a.cur, a.cur, a.tick);
+  const MsTileRec *rec = net.tiles_v + blockIdx.x;
+  const MsTile tl = rec->t;
+  const MsView st = ms_view(&rec->s, a.cur, a.cur, a.tick);
   const int tid = threadIdx.x, s = tid >> 3, rq = tid & 7;
   const int trow = tid >> 2, tq = tid & 3;           // transposed phase: row of the tile, group of 8 streams
 
@@ -409,8 +417,9 @@ __global__ __launch_bounds__(256) void ms_vec_kernel(MsNet net, MsTick a) {
 __global__ __launch_bounds__(256) void ms_infer_kernel(MsNet net, MsTick a) {
   constexpr int NB = kMsRW / 16;   // 16-row blocks per wave
   __shared__ __attribute__((aligned(16))) unsigned short xs[2][kMsS * kMsXPitch];
-  const MsTile tl = net.tiles_i[blockIdx.x];
-  const MsView st = ms_view(net.stages + tl.stage, a.cur, a.cur ^ 1, a.tick);
+  const MsTileRec *rec = net.tiles_i + blockIdx.x;
+  const MsTile tl = rec->t;
+  const MsView st = ms_view(&rec->s, a.cur, a.cur ^ 1, a.tick);
   const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6, li = lane & 15, g = lane >> 4;
   const bf16_t *xq = st.is_first ? nullptr : st.xq_fwd;   // what the stage in front published one tick earlier
   const int r0 = tl.a + kMsRW * wv;                    // out_pad is a multiple of the tile: always in range
@@ -973,8 +982,9 @@ __device__ __forceinline__ void ms_mat_tile(const MsNet &net, const MsTick &a, c
 template <int MODE, int OPT>
 __global__ __launch_bounds__(64 * kMsNWM) void ms_mat_kernel(MsNet net, MsTick a) {
   __shared__ __attribute__((aligned(16))) float zred[2][kMsNWM][1024];
-  const MsTile tl = (MODE == 0 ? net.tiles_m : net.tiles_f)[blockIdx.x];
-  const MsView st = ms_view(net.stages + tl.stage, a.cur, a.fhalf);
+  const MsTileRec *rec = (MODE == 0 ? net.tiles_m : net.tiles_f) + blockIdx.x;
+  const MsTile tl = rec->t;
+  const MsView st = ms_view(&rec->s, a.cur, a.fhalf);
   const int tid = threadIdx.x;
   if (MODE == 0 && tl.kind == 2) {
     // a2 for the last stage: 64 of its rows

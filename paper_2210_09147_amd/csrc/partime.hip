@@ -1035,8 +1035,7 @@ struct partime_ctx {
   // multi-stream path
   bool ms = false;
   MsNet msnet{};
-  MsStage *d_ms_stages = nullptr;
-  MsTile *d_ms_tiles = nullptr;
+  MsTileRec *d_ms_tiles = nullptr;
   unsigned int *d_ms_head_ctr = nullptr;
   unsigned int ms_head_count = 0;       // what the counter reads once every head tile launched so far is done
   int ms_n_head = 0;                    // head tiles per learning tick
@@ -1124,7 +1123,6 @@ void free_ctx(partime_ctx *c) {
   if (c->d_rb_stages) (void)hipFree(c->d_rb_stages);
   if (c->d_rb_tiles) (void)hipFree(c->d_rb_tiles);
   if (c->d_rb_loss_s) (void)hipFree(c->d_rb_loss_s);
-  if (c->d_ms_stages) (void)hipFree(c->d_ms_stages);
   if (c->d_ms_tiles) (void)hipFree(c->d_ms_tiles);
   if (c->d_ms_head_ctr) (void)hipFree(c->d_ms_head_ctr);
   if (c->d_ms_hstat) (void)hipFree(c->d_ms_hstat);
@@ -1513,11 +1511,13 @@ int init_multistream(partime_ctx *c, const float *const *w_host, const float *co
     c->n_tiles_f = (int)all.size() - at;
     c->ms_tiles_f_off = at;
   }
-  MS_TRY(hipMalloc(reinterpret_cast<void **>(&c->d_ms_stages), sizeof(MsStage) * NL));
-  MS_TRY(hipMemcpy(c->d_ms_stages, sd.data(), sizeof(MsStage) * NL, hipMemcpyHostToDevice));
-  MS_TRY(hipMalloc(reinterpret_cast<void **>(&c->d_ms_tiles), sizeof(MsTile) * all.size()));
-  MS_TRY(hipMemcpy(c->d_ms_tiles, all.data(), sizeof(MsTile) * all.size(), hipMemcpyHostToDevice));
-  c->msnet.stages = c->d_ms_stages;
+  {
+    // every tile carries a copy of its layer's record (one memory round trip less at the start of every work-group)
+    std::vector<MsTileRec> recs(all.size());
+    for (size_t q = 0; q < all.size(); ++q) { recs[q].t = all[q]; recs[q].s = sd[all[q].stage]; }
+    MS_TRY(hipMalloc(reinterpret_cast<void **>(&c->d_ms_tiles), sizeof(MsTileRec) * recs.size()));
+    MS_TRY(hipMemcpy(c->d_ms_tiles, recs.data(), sizeof(MsTileRec) * recs.size(), hipMemcpyHostToDevice));
+  }
   c->msnet.tiles_v = c->msnet.tiles_m = c->msnet.tiles_f = c->msnet.tiles_i = c->d_ms_tiles;   // set per launch
   c->msnet.loss = c->cfg.loss;
   c->msnet.out_dim = c->out_dim;
