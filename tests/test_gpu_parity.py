@@ -475,11 +475,14 @@ def test_config4_full_size_multistream():
     full_size_forced(w, w.depth + 1, bf16=True, synthetic=True, rel_step=0.1)
 
 
-def test_config4_full_size_multistream_two_layers_per_stage():
-    """The same network as four stages of two layers (Eq. 3-5), at full size, from a synthetic full pipeline: forward-only
-    matrix launches, kept pre-activations and in-stage deltas at 4096-wide layers."""
+def test_full_width_multistream_two_layers_per_stage():
+    """Layers of the benchmark's width as two stages of two layers (Eq. 3-5), 32 streams, from a synthetic full pipeline:
+    forward-only matrix launches, kept pre-activations and in-stage deltas at 4096-wide layers; the checked tick is an
+    odd one (rows walked bottom-up).  (Workload 21, all eight layers in four stages, is what bench.py times.)"""
     w = ps.workload(21)
-    full_size_forced(w, w.depth + 1, bf16=True, synthetic=True, rel_step=0.1)
+    w.layers = ps.mlp([4096, 4096, 4096, 4096, 1000], ps.ACT_RELU)
+    w.balance = [2, 2]
+    full_size_forced(w, w.depth + 1, bf16=True, synthetic=True, rel_step=0.1, n_forced=1)
 
 
 # ----------------------------------------------------------------------------- replay batch: 64 and more streams
@@ -533,11 +536,11 @@ def test_batched_unpadded_sizes(adam):
 
 
 def test_batched_full_width_short_run(monkeypatch):
-    """Layers of the benchmark's width (4096, last one 4096 -> 1000) under a replay batch of 256 with Adam: three
-    stages, a few ticks past the fill (the oracle needs about 25 GFLOP in plain loops per tick)."""
+    """Layers of the benchmark's width (4096, last one 4096 -> 1000) under a replay batch of 256 with Adam: two
+    stages, one tick past the fill (the oracle needs about 15 GFLOP in plain loops per tick)."""
     monkeypatch.setenv("PARTIME_RB_TN", "128")   # the tile width of the 8-stage benchmark configuration
     w = ps.workload(12)
-    w.layers = ps.mlp([4096, 4096, 4096, 1000], ps.ACT_RELU)
+    w.layers = ps.mlp([4096, 4096, 1000], ps.ACT_RELU)
     full_size_forced(w, w.depth + 1, bf16=True, adam=w.adam, synthetic=True, rel_step=0.1, n_forced=1)
 
 
@@ -858,8 +861,8 @@ def test_conv_several_layers_per_stage(balance, act):
 
 
 def test_conv_deep_stages_medium():
-    """Twelve conv layers at 64 x 64 in three stages of four, plus the head: long in-stage chains."""
-    wl = conv_workload(3, 64, 64, 12, 10, lr=0.01, seed=8)
+    """Twelve conv layers at 32 x 64 in three stages of four, plus the head: long in-stage chains."""
+    wl = conv_workload(3, 32, 64, 12, 10, lr=0.01, seed=8)
     wl.balance = [4, 4, 4, 1]
     run_pair(wl, 9, tol=CONV_TOL)
 
