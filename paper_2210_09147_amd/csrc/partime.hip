@@ -83,9 +83,15 @@ struct TileDev {
   int stage, row0, nrows, part;
 };
 
+// what a work-group reads first: its tile and, in the same record, a copy of the layer's record (with the layer records
+// in an array of their own it would read the tile, then the layer, then its data: three cold round trips in a row)
+struct TileRec {
+  TileDev t;
+  StageDev s;
+};
+
 struct NetDev {
-  const StageDev *stages;
-  const TileDev *tiles;
+  const TileRec *tiles;
   int depth, n_tiles, loss, out_dim, xs_len, red_len, max_rows;
   float lr;
   float beta1, beta2, eps;   // Adam
@@ -713,8 +719,9 @@ template <typename WT>
 constexpr int rows_per_iter_adam(int nch) { return rows_per_iter<WT>(nch) >= 4 ? rows_per_iter<WT>(nch) / 4 : 1; }
 
 template <typename WT, bool LEARN, int NW, int NBUF, bool COH, int OPT = 0>
-__device__ __forceinline__ void dispatch_tile(const NetDev &net, const TileDev &tl, const TickArgs &a, float *lds) {
-  const StageDev *sp = net.stages + tl.stage;
+__device__ __forceinline__ void dispatch_tile(const NetDev &net, const TileRec *rec, const TickArgs &a, float *lds) {
+  const TileDev tl = rec->t;
+  const StageDev *sp = &rec->s;
   StageView st;
   st.W = sp->W; st.b = sp->b;
   st.in_dim = sp->in_dim; st.out_dim = sp->out_dim; st.ld = sp->ld;
@@ -811,8 +818,7 @@ __global__ __launch_bounds__(NW * 64) void persistent_kernel(NetDev net, BlockAr
     a.loss1 = pa.loss ? pa.loss + i : pa.dummy;
     for (int tile = blockIdx.x; tile < net.n_tiles; tile += gridDim.x) {
       __syncthreads();   // the previous tile's LDS contents are dead from here on
-      const TileDev tl = net.tiles[tile];
-      dispatch_tile<WT, LEARN, NW, NBUF, true>(net, tl, a, lds);
+      dispatch_tile<WT, LEARN, NW, NBUF, true>(net, net.tiles + tile, a, lds);
     }
     if (i + 1 < pa.n_ticks) {
       if (!grid_barrier(pa, pa.bar_base + (unsigned long long)(i + 1) * gridDim.x, &flag)) return;
@@ -825,8 +831,7 @@ __global__ __launch_bounds__(NW * 64) void tick_kernel(NetDev net, TickArgs a) {
   // (aligned: behind a static LDS variable of the kernel the array would otherwise start at an odd word, and every 16-byte
   // access to it would be a misaligned one: the 8 x 4096 fp32 workload ran 8 % slower that way)
   extern __shared__ __attribute__((aligned(16))) float lds[];
-  const TileDev tl = net.tiles[blockIdx.x];
-  dispatch_tile<WT, LEARN, NW, NBUF, false, OPT>(net, tl, a, lds);
+  dispatch_tile<WT, LEARN, NW, NBUF, false, OPT>(net, net.tiles + blockIdx.x, a, lds);
 }
 
 __global__ void fill_kernel(float *p, int n, float v) {
@@ -1005,9 +1010,8 @@ struct partime_ctx {
   int64_t ring_period = 1;              // least common multiple of the lengths of all skip rings: the kernels choose
                                         // ring slots from the tick number modulo this
   NetDev net{};
-  StageDev *d_stages = nullptr;
-  TileDev *d_tiles = nullptr;
-  TileDev *d_tiles_inf = nullptr;       // inference-only tile list (bf16 weights: half-size tiles, two per compute unit)
+  TileRec *d_tiles = nullptr;
+  TileRec *d_tiles_inf = nullptr;       // inference-only tile list (bf16 weights: half-size tiles, two per compute unit)
   int n_tiles_inf = 0;
   float *d_lossp = nullptr;
   float *d_dummy = nullptr;
@@ -1107,7 +1111,6 @@ void free_ctx(partime_ctx *c) {
     for (float *q : {s.mW, s.vW, s.mb, s.vb, s.skip_ring, s.serr_ring})
       if (q) (void)hipFree(q);
   }
-  if (c->d_stages) (void)hipFree(c->d_stages);
   if (c->d_tiles) (void)hipFree(c->d_tiles);
   if (c->d_tiles_inf) (void)hipFree(c->d_tiles_inf);
   if (c->d_lossp) (void)hipFree(c->d_lossp);
@@ -2244,10 +2247,16 @@ int partime_init(const partime_config *cfg, const float *const *w_host, const fl
         d.serr_in = t.serr_ring; d.serr_in_n = t.skip_delay + 1; d.serr_in_d = t.skip_delay;
       }
   }
-  INIT_TRY(hipMalloc(&c->d_stages, sizeof(StageDev) * NL));
-  INIT_TRY(hipMemcpy(c->d_stages, sd.data(), sizeof(StageDev) * NL, hipMemcpyHostToDevice));
-  INIT_TRY(hipMalloc(&c->d_tiles, sizeof(TileDev) * c->tiles.size()));
-  INIT_TRY(hipMemcpy(c->d_tiles, c->tiles.data(), sizeof(TileDev) * c->tiles.size(), hipMemcpyHostToDevice));
+  auto with_layers = [&](const std::vector<TileDev> &tl) {
+    std::vector<TileRec> r(tl.size());
+    for (size_t q = 0; q < tl.size(); ++q) { r[q].t = tl[q]; r[q].s = sd[tl[q].stage]; }
+    return r;
+  };
+  {
+    const std::vector<TileRec> recs = with_layers(c->tiles);
+    INIT_TRY(hipMalloc(&c->d_tiles, sizeof(TileRec) * recs.size()));
+    INIT_TRY(hipMemcpy(c->d_tiles, recs.data(), sizeof(TileRec) * recs.size(), hipMemcpyHostToDevice));
+  }
   if (c->cmax == 1 && c->cfg.w_dtype == PT_BF16 && c->tiles_per_cu == 1 && c->cfg.exec_mode != PT_EXEC_PERSISTENT) {
     // Inference with bf16 rows: a wave has half the bytes of an fp32 row in flight and nothing to write, and two
     // work-groups of half the rows per compute unit were measured 20 % faster (16 x 2048 x 2048: 25.9 against 30.9 us
@@ -2273,8 +2282,9 @@ int partime_init(const partime_config *cfg, const float *const *w_host, const fl
         ti.push_back(t);
       }
     c->n_tiles_inf = (int)ti.size();
-    INIT_TRY(hipMalloc(&c->d_tiles_inf, sizeof(TileDev) * ti.size()));
-    INIT_TRY(hipMemcpy(c->d_tiles_inf, ti.data(), sizeof(TileDev) * ti.size(), hipMemcpyHostToDevice));
+    const std::vector<TileRec> recs = with_layers(ti);
+    INIT_TRY(hipMalloc(&c->d_tiles_inf, sizeof(TileRec) * recs.size()));
+    INIT_TRY(hipMemcpy(c->d_tiles_inf, recs.data(), sizeof(TileRec) * recs.size(), hipMemcpyHostToDevice));
   }
   const int pl = c->stages[NL - 1].n_parts;
   INIT_TRY(hipMalloc(&c->d_lossp, sizeof(float) * kLossSlots * pl));
@@ -2285,7 +2295,6 @@ int partime_init(const partime_config *cfg, const float *const *w_host, const fl
     INIT_TRY(hipMemset(c->d_hist[p], 0, std::max<size_t>(1, (size_t)c->k) * c->tgt_bytes));
   }
 
-  c->net.stages = c->d_stages;
   c->net.tiles = c->d_tiles;
   c->net.depth = NL;
   c->net.n_tiles = (int)c->tiles.size();
