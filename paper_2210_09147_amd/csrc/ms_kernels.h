@@ -86,7 +86,7 @@ struct MsStage {
   int n_ct;
   float *zbuf;               // [S][out_pad] pre-activations of this tick: last layer (the loss head reads them) and layers
                              // that are not the last of their stage (their delta is formed later in the tick)
-  bf16_t *dlt;               // [S][out_pad] delta
+  bf16_t *dlt;               // delta as the matrix tiles' operand of E: [block of 32 rows][16 streams half h][lane][8], see ms_put_delta
   bf16_t *dltT;              // [out_pad][S]
   const bf16_t *xq_in[2];    // rnd(stage input) [S][in_pad], published by the previous stage (NULL: first stage)
   bf16_t *xq_out[2];         // rnd(stage output) [S][out_pad] for the next stage (NULL: last stage)
@@ -222,6 +222,18 @@ __device__ __forceinline__ float ms_step(const MsNet &net, const MsTick &a, floa
   m = fmaf(net.beta1, m, (1.f - net.beta1) * g);
   v = fmaf(net.beta2, v, (1.f - net.beta2) * g * g);
   return w - a.adam_c1 * m / (sqrtf(v) * a.adam_c2 + net.eps);
+}
+
+// delta in the order the matrix tiles load it as operand of E = W^T delta: per block of 32 rows and half h of the streams one
+// 16-byte piece per lane (g = lane / 16, li = lane % 16): rows 4 g .. 4 g + 3 and 16 + 4 g .. 16 + 4 g + 3 of the block at
+// stream 16 h + li -- 1 KiB of consecutive memory per request of a wave.  (Kept as [S][out_pad] the same operand took
+// four 8-byte requests per lane over 16 rows of memory 8 KiB apart.)  A vector thread holds rows r .. r + 7 of stream s,
+// r a multiple of 8: two 8-byte pieces of neighbouring lanes.
+__device__ __forceinline__ void ms_put_delta(bf16_t *dlt, int s, int r, const unsigned int (&pd)[4]) {
+  const int rr = r & 31, g0 = (rr >> 2) & 3, hi = rr >> 4;
+  bf16_t *p = dlt + ((size_t)((r >> 5) * 2 + (s >> 4)) * 64 + g0 * 16 + (s & 15)) * 8 + hi * 4;
+  stg8(p, make_uint2(pd[0], pd[1]));
+  stg8(p + 16 * 8, make_uint2(pd[2], pd[3]));   // rows r + 4 .. r + 7: the next g
 }
 
 // acc[0..7] += the 8 consecutive floats at p0 + q * plane for q = 0 .. n - 1, added in ascending order.  The planes are
@@ -376,7 +388,7 @@ __global__ __launch_bounds__(256) void ms_vec_kernel(MsNet net, MsTick a) {
     }
 #pragma unroll
     for (int j = 0; j < 4; ++j) pd[j] = pack_bf16(g[2 * j] * act_der(st.act, z[2 * j]), g[2 * j + 1] * act_der(st.act, z[2 * j + 1]));
-    stg16(st.dlt + (size_t)s * st.out_pad + r, make_uint4(pd[0], pd[1], pd[2], pd[3]));
+    ms_put_delta(st.dlt, s, r, pd);
   }
 #pragma unroll
   for (int j = 0; j < 4; ++j) {
@@ -643,7 +655,7 @@ __device__ __forceinline__ void ms_head_tile(const MsNet &net, const MsTick &a, 
   for (int j = 0; j < 4; ++j)
     pd[j] = pack_bf16(r + 2 * j < st.out_dim ? gg[2 * j] * act_der(ACT, z[2 * j]) : 0.f,
                       r + 2 * j + 1 < st.out_dim ? gg[2 * j + 1] * act_der(ACT, z[2 * j + 1]) : 0.f);
-  stg16(st.dlt + (size_t)s * st.out_pad + r, make_uint4(pd[0], pd[1], pd[2], pd[3]));
+  ms_put_delta(st.dlt, s, r, pd);
 #pragma unroll
   for (int j = 0; j < 4; ++j) {
     tr[(8 * rq + 2 * j) * kMsS + s] = (unsigned short)(pd[j] & 0xffffu);
@@ -760,11 +772,7 @@ __device__ __forceinline__ void ms_mat_tile(const MsNet &net, const MsTick &a, c
         k.w[sb][b] = ldg16(st.W + wbase + (size_t)(r0 >> 5) * kMsBlk + (2 * sb + b) * 512);
     if (MODE == 0) {
 #pragma unroll
-      for (int h = 0; h < 2; ++h) {
-        const bf16_t *dp = st.dlt + (size_t)(16 * h + li) * st.out_pad + r0 + 4 * g;
-        const uint2 lo = ldg8(dp), hi = ldg8(dp + 16);
-        k.de[h] = make_uint4(lo.x, lo.y, hi.x, hi.y);
-      }
+      for (int h = 0; h < 2; ++h) k.de[h] = ldg16(st.dlt + ((size_t)((r0 >> 5) * 2 + h) * 64 + lane) * 8);
 #pragma unroll
       for (int b = 0; b < 2; ++b) k.du[b] = ldg16(st.dltT + (size_t)(r0 + 16 * b + li) * kMsS + g * 8);
     }
