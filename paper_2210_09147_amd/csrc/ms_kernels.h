@@ -82,7 +82,7 @@ struct MsStage {
   int in_dim, out_dim, in_pad, out_pad, act, is_last, is_first;
   int fold;                  // first layer of its stage: its matrix launch also forms the coming tick's pre-activations
   float *out_act[2];         // [S][out_pad] (NULL: last stage, output goes to the caller)
-  float *zp;                 // [n_ct][S][out_pad] partial pre-activations of the coming tick, one plane per column tile
+  float *zp;                 // [n_ct] planes of S x out_pad partial pre-activations of the coming tick (order: ms_poff), one per column tile
   int n_ct;
   float *zbuf;               // [S][out_pad] pre-activations of this tick: last layer (the loss head reads them) and layers
                              // that are not the last of their stage (their delta is formed later in the tick)
@@ -94,9 +94,9 @@ struct MsStage {
   bf16_t *xT_out[2];         // rnd(stage output) transposed [out_pad][S] (NULL: last stage)
   bf16_t *xT0;               // first stage only: rnd(x(t)) transposed [in_pad][S]
   bf16_t *xq0;               // first stage only: rnd(x of the coming tick) [S][in_pad]
-  const float *gin[2];       // error planes of the next stage [n_gparts][S][out_pad]
+  const float *gin[2];       // error planes of the next stage: [n_gparts] planes of S x out_pad (order: ms_poff)
   int n_gparts;
-  float *eout[2];            // this stage's error planes [n_rt][S][in_pad] (NULL for the first stage)
+  float *eout[2];            // this stage's error planes: [n_rt] planes of S x in_pad (NULL for the first stage)
   int n_rt, tr;              // row tiles of the matrix launch (= error planes) and their height
   // skip connections (Sec. V-C): a layer that adds the output of an earlier layer reads it with the delay of the stage
   // boundaries in between and hands the gradient at its own output back with the same delay.  Both wait in rings of
@@ -236,18 +236,26 @@ __device__ __forceinline__ void ms_put_delta(bf16_t *dlt, int s, int r, const un
   stg8(p + 16 * 8, make_uint2(pd[2], pd[3]));   // rows r + 4 .. r + 7: the next g
 }
 
-// acc[0..7] += the 8 consecutive floats at p0 + q * plane for q = 0 .. n - 1, added in ascending order.  The planes are
-// requested CH at a time, at clamped addresses: one request per trip of a loop with a run-time bound would be one memory
-// round trip after the other.
+// Partial-sum planes (pre-activations per column tile, errors per row tile) are [S][pad] values kept in the order the
+// matrix tiles produce them: per 16 values of the padded axis and half h of the streams one 16-byte piece per lane of
+// the matrix-core result layout (lane = 16 g + li holds values 4 g .. 4 g + 3 at stream 16 h + li), so a wave writes
+// 1 KiB of consecutive memory (rows of [S][pad] would take 64-byte pieces 16 KiB apart).  Element (stream s, index i):
+__host__ __device__ inline size_t ms_poff(int s, int i) {
+  return ((size_t)((i >> 4) * 2 + (s >> 4)) * 64 + ((i >> 2) & 3) * 16 + (s & 15)) * 4 + (i & 3);
+}
+// acc[0..7] += the values i .. i + 7 (i a multiple of 8) of stream s in planes q = 0 .. n - 1, added in ascending order.
+// The planes are requested CH at a time, at clamped addresses: one request per trip of a loop with a run-time bound would
+// be one memory round trip after the other.
 template <int CH>
-__device__ __forceinline__ void ms_add_planes(const float *p0, int n, size_t plane, float (&acc)[8]) {
+__device__ __forceinline__ void ms_add_planes(const float *planes, int s, int i, int n, size_t plane, float (&acc)[8]) {
+  const float *p0 = planes + ms_poff(s, i);   // values i .. i + 3; i + 4 .. i + 7 sit one g further: 64 floats on
   for (int q0 = 0; q0 < n; q0 += CH) {
     float4 u[CH][2];
 #pragma unroll
     for (int i = 0; i < CH; ++i) {
       const float *p = p0 + (size_t)min(q0 + i, n - 1) * plane;
       u[i][0] = ldg_f4(p);
-      u[i][1] = ldg_f4(p + 4);
+      u[i][1] = ldg_f4(p + 64);
     }
 #pragma unroll
     for (int i = 0; i < CH; ++i) {
@@ -312,7 +320,7 @@ __global__ __launch_bounds__(256) void ms_vec_kernel(MsNet net, MsTick a) {
   if (fwd) {
     const float4 b0 = ldg_f4(st.b + r), b1 = ldg_f4(st.b + r + 4);
     z[0] = b0.x; z[1] = b0.y; z[2] = b0.z; z[3] = b0.w; z[4] = b1.x; z[5] = b1.y; z[6] = b1.z; z[7] = b1.w;
-    ms_add_planes<8>(st.zp + (size_t)s * st.out_pad + r, st.n_ct, plane, z);
+    ms_add_planes<8>(st.zp, s, r, st.n_ct, plane, z);
     if (tl.kind == 3) {   // a layer that is not the last of its stage: delta needs this tick's z later in the tick (Eq. 9)
       stg_f4(st.zbuf + (size_t)s * st.out_pad + r, make_float4(z[0], z[1], z[2], z[3]));
       stg_f4(st.zbuf + (size_t)s * st.out_pad + r + 4, make_float4(z[4], z[5], z[6], z[7]));
@@ -377,7 +385,7 @@ __global__ __launch_bounds__(256) void ms_vec_kernel(MsNet net, MsTick a) {
     // tick (sum of its row-tile planes, Eq. 11 / Eq. 5), delta = rnd(g * phi'(z)) with this tick's z (Eq. 9).
     // Padding rows have z = 0 and g = 0, hence delta = 0.
     float g[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-    ms_add_planes<4>(st.gin_prev + (size_t)s * st.out_pad + r, st.n_gparts, plane, g);
+    ms_add_planes<4>(st.gin_prev, s, r, st.n_gparts, plane, g);
     if (st.serr_in) {    // source of a skip: the delayed gradient of the target joins
       const float4 e0 = ldg_f4(st.serr_in + (size_t)s * st.out_pad + r), e1 = ldg_f4(st.serr_in + (size_t)s * st.out_pad + r + 4);
       g[0] += e0.x; g[1] += e0.y; g[2] += e0.z; g[3] += e0.w; g[4] += e1.x; g[5] += e1.y; g[6] += e1.z; g[7] += e1.w;
@@ -940,8 +948,8 @@ __device__ __forceinline__ void ms_mat_tile(const MsNet &net, const MsTick &a, c
 #pragma unroll
       for (int w = 1; w < kMsNWM; ++w) t += *reinterpret_cast<const f32x4_t *>(&zred[slot][w][tid * 4]);
       // position tid = (b, h, lane'): rows r0 + 16 b + 4 g' + j of stream 16 h + li'
-      const int b = tid >> 7, h = (tid >> 6) & 1, l2 = tid & 63;
-      float *dst = st.zp + ((size_t)tl.b * kMsS + 16 * h + (l2 & 15)) * st.out_pad + r0 + 16 * b + 4 * (l2 >> 4);
+      // which in the planes' order is simply the tid-th 16-byte piece of the block's 4 KiB
+      float *dst = st.zp + (size_t)tl.b * kMsS * st.out_pad + ((size_t)(r0 >> 5) * 256 + tid) * 4;
       stg_f4(dst, make_float4(t[0], t[1], t[2], t[3]));
     }
   };
@@ -982,7 +990,7 @@ __device__ __forceinline__ void ms_mat_tile(const MsNet &net, const MsTick &a, c
     for (int c = 0; c < 2; ++c)
 #pragma unroll
       for (int h = 0; h < 2; ++h) {
-        float *dst = plane + (size_t)(16 * h + li) * st.in_pad + c0 + 32 * sb + 16 * c + 4 * g;
+        float *dst = plane + ((size_t)(((c0 + 32 * sb + 16 * c) >> 4) * 2 + h) * 64 + lane) * 4;
         stg_f4(dst, make_float4(eacc[sb][c][h][0], eacc[sb][c][h][1], eacc[sb][c][h][2], eacc[sb][c][h][3]));
       }
 }

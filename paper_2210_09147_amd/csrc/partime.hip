@@ -2858,7 +2858,7 @@ int partime_get_buffer(partime_ctx *ctx, int which, int stage, int half, float *
       for (int q = 0; q < S; ++q)
         for (int k = 0; k < s.in_dim; ++k) {
           float t = 0.f;
-          for (int p = 0; p < s.n_rt; ++p) t += tmp[((size_t)p * S + q) * s.in_pad + k];
+          for (int p = 0; p < s.n_rt; ++p) t += tmp[(size_t)p * S * s.in_pad + ms_poff(q, k)];
           host[(size_t)q * s.in_dim + k] = t;
         }
     }
@@ -2948,7 +2948,8 @@ int partime_set_buffer(partime_ctx *ctx, int which, int stage, int half, const f
       HIP_TRY(hipMemcpy(s.xT[half], t16.data(), t16.size() * 2, hipMemcpyHostToDevice));
     } else {
       std::vector<float> tmp(s.err_elems, 0.f);   // plane 0 carries the values, the other planes are zero
-      for (int q = 0; q < S; ++q) std::memcpy(&tmp[(size_t)q * s.in_pad], host + (size_t)q * s.in_dim, (size_t)s.in_dim * 4);
+      for (int q = 0; q < S; ++q)
+        for (int k = 0; k < s.in_dim; ++k) tmp[ms_poff(q, k)] = host[(size_t)q * s.in_dim + k];
       HIP_TRY(hipMemcpy(s.err_buf[half], tmp.data(), tmp.size() * 4, hipMemcpyHostToDevice));
     }
     return PT_OK;
