@@ -1500,29 +1500,29 @@ int init_multistream(partime_ctx *c, const float *const *w_host, const float *co
     }
     {
       // Work-group i of a launch runs on die i mod 8, each die with its own L2, and the column tiles of one row tile read
-      // the same deltas: eight row tiles at a time are dealt out so that all column tiles of a row tile land on one die
-      // (index within the chunk = column tile * 8 + row tile).  Row tiles that do not fill a chunk of equal widths keep the
-      // plain order.
-      std::vector<std::pair<int, int>> groups;   // (layer, row tile)
-      for (int i = 0; i < NL; ++i)
-        if (back_of(c->stages[i]) == back && i != NL - 1)
-          for (int p = 0; p < c->stages[i].n_rt; ++p) groups.push_back({i, p});
-      size_t g = 0;
-      while (g < groups.size()) {
-        bool chunk = g + 8 <= groups.size() && (all.size() - c->ms_mb[back].first) % 8 == 0;   // (dies count from the launch's start)
-        for (size_t u = 1; chunk && u < 8; ++u) chunk = c->stages[groups[g + u].first].n_ct == c->stages[groups[g].first].n_ct;
-        if (chunk) {
-          const int n_ct = c->stages[groups[g].first].n_ct;
-          for (int q = 0; q < n_ct; ++q)
-            for (size_t u = 0; u < 8; ++u) all.push_back(MsTile{groups[g + u].first, groups[g + u].second, q, 0});
-          g += 8;
-        } else {
-          for (int q = 0; q < c->stages[groups[g].first].n_ct; ++q) all.push_back(MsTile{groups[g].first, groups[g].second, q, 0});
-          g += 1;
+      // the same deltas: row tiles are dealt out eight at a time (then four, two, one for what is left), column tile by
+      // column tile, so that the column tiles of a row tile are 8 (4, 2) places apart and land on one die (two, four).
+      auto deal = [&](const std::vector<std::pair<int, int>> &groups) {   // (layer, row tile)
+        size_t g = 0;
+        while (g < groups.size()) {
+          size_t n = 8;
+          for (;; n /= 2) {
+            bool ok = g + n <= groups.size();
+            for (size_t u = 1; ok && u < n; ++u) ok = c->stages[groups[g + u].first].n_ct == c->stages[groups[g].first].n_ct;
+            if (ok) break;
+          }
+          for (int q = 0; q < c->stages[groups[g].first].n_ct; ++q)
+            for (size_t u = 0; u < n; ++u) all.push_back(MsTile{groups[g + u].first, groups[g + u].second, q, 0});
+          g += n;
         }
-      }
+      };
+      std::vector<std::pair<int, int>> groups, last;
+      for (int i = 0; i < NL; ++i)
+        if (back_of(c->stages[i]) == back)
+          for (int p = 0; p < c->stages[i].n_rt; ++p) (i == NL - 1 ? last : groups).push_back({i, p});
+      deal(groups);
+      deal(last);   // (the last layer's tiles wait for the loss head: at the end of the launch)
     }
-    if (back == 0) mat_tiles(NL - 1);
     close_list(c->ms_mb, back);
   }
   {
