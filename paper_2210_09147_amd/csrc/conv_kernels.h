@@ -115,7 +115,10 @@ __device__ __forceinline__ f32x16_t mfma32(float a, float b, f32x16_t c) {
 // conv as implicit GEMM: out[64][tile of 256 pixels] = Wmat[64][c * 9] * patches[c * 9][256]
 // four waves: wave w takes output channels 32 (w & 1) .. +32 and the four 32-pixel blocks 4 (w >> 1) .. +3
 // ------------------------------------------------------------------------------------------------
-template <int MODE, bool LEARN, int LW>
+// RES: some layer of the pipeline has a residual connection.  A template parameter because the ring handling in the
+// epilogues costs every tile registers and instructions (250 instead of 182 registers in the forward kernel; the
+// 150-layer workload ran 7 % slower for it) that a pipeline without residual connections need not pay.
+template <int MODE, bool LEARN, int LW, bool RES>
 __global__ __launch_bounds__(256, 2) void cv_conv_kernel(CvNet net, CvTick a) {
   // (aligned: behind a static LDS variable of the kernel the array would otherwise start at an odd word, and every 16-byte
   // access to it would be a misaligned one: the 8 x 4096 fp32 workload ran 8 % slower that way)
@@ -214,7 +217,7 @@ __global__ __launch_bounds__(256, 2) void cv_conv_kernel(CvNet net, CvTick a) {
   // its epilogue; BWD: the layer in front, whose delta this launch forms) is in hand
   const float *skip_in = nullptr, *serr_in = nullptr;
   float *skip_out = nullptr, *serr_out = nullptr;
-  {
+  if constexpr (RES) {
     const CvStage *rp = MODE == CV_FWD ? sp : sp - 1;
     if (MODE == CV_FWD || pred_delta) {
       const size_t frame = (size_t)rp->co_pad * H * sp->W;

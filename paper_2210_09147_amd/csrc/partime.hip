@@ -1818,21 +1818,28 @@ hipError_t launch2(const void *k, int grid, int block, size_t lds, hipStream_t s
 }
 
 // the conv kernels are compiled per frame width (every LDS offset is then an immediate)
-template <int LW>
+template <int LW, bool RES>
 void cv_set_kernels(partime_ctx *c) {
-  c->cv_k_fwd[0] = reinterpret_cast<const void *>(&cv_conv_kernel<CV_FWD, false, LW>);
-  c->cv_k_fwd[1] = reinterpret_cast<const void *>(&cv_conv_kernel<CV_FWD, true, LW>);
-  c->cv_k_bwd[0] = reinterpret_cast<const void *>(&cv_conv_kernel<CV_BWD, false, LW>);
-  c->cv_k_bwd[1] = reinterpret_cast<const void *>(&cv_conv_kernel<CV_BWD, true, LW>);
+  c->cv_k_fwd[0] = reinterpret_cast<const void *>(&cv_conv_kernel<CV_FWD, false, LW, RES>);
+  c->cv_k_fwd[1] = reinterpret_cast<const void *>(&cv_conv_kernel<CV_FWD, true, LW, RES>);
+  c->cv_k_bwd[0] = reinterpret_cast<const void *>(&cv_conv_kernel<CV_BWD, false, LW, RES>);
+  c->cv_k_bwd[1] = reinterpret_cast<const void *>(&cv_conv_kernel<CV_BWD, true, LW, RES>);
   c->cv_k_wg = LW >= 6 ? reinterpret_cast<const void *>(&cv_wgrad_kernel<64>) : reinterpret_cast<const void *>(&cv_wgrad_kernel<32>);
 }
-void cv_pick_kernels(partime_ctx *c, int W) {
+template <bool RES>
+void cv_pick_width(partime_ctx *c, int W) {
   switch (W) {
-    case 32: cv_set_kernels<5>(c); break;
-    case 64: cv_set_kernels<6>(c); break;
-    case 128: cv_set_kernels<7>(c); break;
-    default: cv_set_kernels<8>(c); break;
+    case 32: cv_set_kernels<5, RES>(c); break;
+    case 64: cv_set_kernels<6, RES>(c); break;
+    case 128: cv_set_kernels<7, RES>(c); break;
+    default: cv_set_kernels<8, RES>(c); break;
   }
+}
+void cv_pick_kernels(partime_ctx *c, int W) {
+  bool res = false;
+  for (const pt_layer &l : c->layers) res = res || l.skip_from >= 0;
+  if (res) cv_pick_width<true>(c, W);
+  else cv_pick_width<false>(c, W);
 }
 
 int init_conv(partime_ctx *c, const float *const *w_host, const float *const *b_host, const int *balance) {
@@ -1950,14 +1957,18 @@ int init_conv(partime_ctx *c, const float *const *w_host, const float *const *b_
     }
     // forward launch number pos; backward-data launch number cnt - 1 - pos (none for the very first layer:
     // nobody needs the error of the frame)
+    // Work-group i of a launch runs on die i mod 8 and neighbouring row tiles of a layer read the same halo rows: the n row
+    // tiles of a layer are dealt out so that a die gets n / 8 neighbours (position j * 8 + d <-> row tile d * (n / 8) + j)
+    auto dealt = [](int n, int i) { return n % 8 ? i : (i % 8) * (n / 8) + i / 8; };
+    const int n_rows = H / TR;
     for (int ob = 0; ob < v.co_pad / kCvCo; ++ob)
-      for (int y = 0; y < H; y += TR) tf[v.pos].push_back(CvTile{h, y, ob, 0});
+      for (int i = 0; i < n_rows; ++i) tf[v.pos].push_back(CvTile{h, dealt(n_rows, i) * TR, ob, 0});
     if (h > 0)
       for (int ib = 0; ib < v.ci_pad / kCvCo; ++ib)
-        for (int y = 0; y < H; y += TR) tb[v.cnt - 1 - v.pos].push_back(CvTile{h, y, ib, 0});
-    for (int band = 0; band < v.n_wt; ++band)
+        for (int i = 0; i < n_rows; ++i) tb[v.cnt - 1 - v.pos].push_back(CvTile{h, dealt(n_rows, i) * TR, ib, 0});
+    for (int i = 0; i < v.n_wt; ++i)
       for (int ib = 0; ib < v.ci_pad / kCvCo; ++ib)
-        for (int ob = 0; ob < v.co_pad / kCvCo; ++ob) tw.push_back(CvTile{h, band, ib, ob});
+        for (int ob = 0; ob < v.co_pad / kCvCo; ++ob) tw.push_back(CvTile{h, dealt(v.n_wt, i), ib, ob});
     c->cv_total_w += v.co_pad * v.c_in * 9 + v.co_pad;
   }
   {
